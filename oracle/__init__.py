@@ -1,0 +1,102 @@
+"""ctypes front end of the CPU attention oracle (oracle/flat_oracle.cpp).
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product package imports this; it is
+for tests/, the smoke check and the benchmark's cpu_baseline leg.  It imports
+nothing from the GPU package either.
+
+`build()` compiles the C++ with g++; `attention()` and `logits_softmax()`
+marshal numpy float64 arrays into it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "flat_oracle.cpp")
+_LIB = os.path.join(_HERE, "libflat_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle into oracle/libflat_oracle.so (rebuilds when the source is newer)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread",
+                               "-ffp-contract=off", "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int64)
+        lib.flat_oracle_hw_threads.restype = ctypes.c_int
+        lib.flat_oracle_attention.restype = ctypes.c_int
+        lib.flat_oracle_attention.argtypes = [dp, dp, dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
+                                              ctypes.c_double, ctypes.c_int, ip, ctypes.c_int64, ctypes.c_int]
+        lib.flat_oracle_logits_softmax.restype = ctypes.c_int
+        lib.flat_oracle_logits_softmax.argtypes = [dp, dp, ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_int,
+                                                   ip, ctypes.c_int64, dp, dp]
+        _lib = lib
+    return _lib
+
+
+def _dptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def hw_threads() -> int:
+    return int(_load().flat_oracle_hw_threads())
+
+
+def attention(Q, K, V, scale: float, mask_kind: int = 0, rows=None, threads: int = 0) -> np.ndarray:
+    """O = softmax_row(Q K^T * scale) V for [B,H,N,d] inputs, in float64.
+
+    `rows` (1-D integer array) restricts the output to those query indices of
+    every head; the result is [B,H,len(rows),d].  `scale` is used as given
+    (pass the float32-rounded value that the GPU entry point receives).
+    """
+    lib = _load()
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    if Q.ndim != 4 or Q.shape != K.shape or Q.shape != V.shape:
+        raise ValueError("Q, K, V must share a [B,H,N,d] shape")
+    B, H, N, d = Q.shape
+    if rows is None:
+        rp, nr = None, N
+    else:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        rp, nr = rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), rows.size
+    O = np.empty((B, H, nr, d), dtype=np.float64)
+    rc = lib.flat_oracle_attention(_dptr(Q), _dptr(K), _dptr(V), _dptr(O), B, H, N, d, float(scale), int(mask_kind),
+                                   rp, nr, int(threads))
+    if rc != 0:
+        raise ValueError(f"flat_oracle_attention rejected its arguments (code {rc})")
+    return O
+
+
+def logits_softmax(Q, K, scale: float, mask_kind: int = 0, rows=None):
+    """(L, A) of one head: Q, K are [N,d]; returns two [len(rows), N] float64 arrays."""
+    lib = _load()
+    Q, K = _f64(Q), _f64(K)
+    N, d = Q.shape
+    rows = np.arange(N, dtype=np.int64) if rows is None else np.ascontiguousarray(rows, dtype=np.int64)
+    L = np.empty((rows.size, N), dtype=np.float64)
+    A = np.empty((rows.size, N), dtype=np.float64)
+    rc = lib.flat_oracle_logits_softmax(_dptr(Q), _dptr(K), N, d, float(scale), int(mask_kind),
+                                        rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), rows.size, _dptr(L), _dptr(A))
+    if rc != 0:
+        raise ValueError(f"flat_oracle_logits_softmax rejected its arguments (code {rc})")
+    return L, A

@@ -1,0 +1,99 @@
+/*
+ * flat_attn.h -- C ABI of the fused-attention library for AMD MI355X (gfx950).
+ *
+ * The library computes, for every (batch, head) of [B,H,N,d] tensors,
+ *
+ *     L = Q K^T * scale        (Logit operator,  paper section 2, step 2)
+ *     A = softmax_row(L)       (row normalisation along the key dimension, step 3 / section 5.2)
+ *     O = A V                  (Attend operator, step 4)
+ *
+ * in two ways:
+ *   - flat_attn_fwd / flat_attn_fwd_f32: the fused, query-row-tiled dataflow of the paper's
+ *     sections 4-5 (shared outer loop over batch, head and row blocks; Logit, softmax and
+ *     Attend interleaved per block) -- the N x N intermediate never leaves the chip;
+ *   - flat_attn_unfused: the operator-by-operator baseline of Fig. "flat_dataflow"(a), with L
+ *     materialised in device memory (GEMM -> row softmax in place -> GEMM).
+ *
+ * Conventions common to all entry points
+ *   - Q, K, V, O are DEVICE pointers to contiguous [B,H,N,d] arrays, d fastest; element type
+ *     bf16 (flat_attn_fwd, flat_attn_unfused) or float (flat_attn_fwd_f32).  All four must
+ *     be 16-byte aligned.  Q, K, V are only read.  O must not overlap Q, K or V.
+ *   - Self-attention: queries and keys both number N.  Any N >= 1 is accepted.  d is 64 or 128.
+ *   - scale multiplies the logits before softmax.
+ *   - mask_kind: FLAT_MASK_NONE, or FLAT_MASK_CAUSAL (key j contributes to query i iff j <= i;
+ *     a masked key has probability exactly 0).
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
+ *     and return without synchronising.
+ *   - The caller owns every buffer.  The library allocates and frees nothing and keeps no
+ *     state between calls; calls from different threads are independent.
+ *   - Return value: FLAT_OK, or a negative flat_status.  Argument checks run before any
+ *     HIP call, so they can be exercised on a machine without a GPU.  FLAT_ERR_HIP reports a
+ *     failed launch; no partial work is rolled back.
+ *   - Results of the fused kernels are bitwise reproducible from run to run (fixed reduction
+ *     order, no atomics).
+ */
+#ifndef FLAT_ATTN_H
+#define FLAT_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FLAT_OK = 0,
+    FLAT_ERR_NULL = -1,        /* a required pointer is NULL */
+    FLAT_ERR_SHAPE = -2,       /* B, H or N is not positive, or B*H*N*N / B*H*N*d overflows */
+    FLAT_ERR_UNSUPPORTED = -3, /* d not in {64,128}, unknown mask_kind or dtype */
+    FLAT_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
+    FLAT_ERR_WORKSPACE = -5,   /* workspace_bytes is smaller than flat_attn_unfused_workspace_bytes() */
+    FLAT_ERR_HIP = -6,         /* the HIP runtime refused a launch */
+    FLAT_ERR_ALIAS = -7        /* O overlaps Q, K or V */
+} flat_status;
+
+typedef enum { FLAT_MASK_NONE = 0, FLAT_MASK_CAUSAL = 1 } flat_mask_kind;
+
+typedef enum { FLAT_DTYPE_BF16 = 0 } flat_dtype;
+
+/*
+ * Fused attention forward, bf16 in / bf16 out, fp32 accumulation (sections 4-5: fused
+ * Logit-softmax-Attend at row granularity).  Probabilities are rounded to bf16 before the
+ * second contraction; row maxima and row sums are kept in fp32.
+ *   Q, K, V: device, const bf16 [B,H,N,d].   O: device, bf16 [B,H,N,d], fully overwritten.
+ */
+int flat_attn_fwd(const void* Q, const void* K, const void* V, void* O,
+                  int B, int H, int N, int d, float scale, int mask_kind, void* stream);
+
+/*
+ * Same dataflow in fp32 throughout (fp32 matrix instructions, fp32 probabilities).
+ *   Q, K, V: device, const float [B,H,N,d].  O: device, float [B,H,N,d].
+ */
+int flat_attn_fwd_f32(const float* Q, const float* K, const float* V, float* O,
+                      int B, int H, int N, int d, float scale, int mask_kind, void* stream);
+
+/*
+ * Unfused baseline (Fig. "flat_dataflow"(a); the off-chip traffic this path pays is the
+ * O(B H N^2) intermediate of section 3.3).  Three launches on `stream`:
+ *   1. L = Q K^T * scale written as fp32 [B,H,N,N] into `workspace`;
+ *   2. each row of L replaced in place by its softmax (masked keys become 0);
+ *   3. O = A V reading the fp32 probabilities back (rounded to bf16 as they are loaded).
+ * workspace: device, 16-byte aligned, at least flat_attn_unfused_workspace_bytes() bytes;
+ *   contents on return are the probabilities A.  dtype: FLAT_DTYPE_BF16.
+ */
+size_t flat_attn_unfused_workspace_bytes(int B, int H, int N, int d, int dtype);
+
+int flat_attn_unfused(const void* Q, const void* K, const void* V, void* O,
+                      int B, int H, int N, int d, float scale, int mask_kind,
+                      void* workspace, size_t workspace_bytes, int dtype, void* stream);
+
+/* Human-readable name of a flat_status value (static storage, never NULL). */
+const char* flat_attn_status_string(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int flat_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLAT_ATTN_H */

@@ -1,0 +1,13 @@
+"""Fused attention for AMD MI355X (gfx950): thin Python binding over the C-ABI library.
+
+The HIP library (libflat_attn.so, built in-tree by `paper_2107_06419_amd.build`) does all the
+work; this package only marshals arguments.  There is no CPU or PyTorch fallback: if the
+library is missing, every call raises.
+"""
+from .binding import (FLAT_MASK_CAUSAL, FLAT_MASK_NONE, FlatAttnError, flat_attn_fwd, flat_attn_fwd_f32,
+                      flat_attn_status_string, flat_attn_unfused, flat_attn_unfused_workspace_bytes,
+                      flat_attn_version, library_path, load_library)
+
+__all__ = ["FLAT_MASK_NONE", "FLAT_MASK_CAUSAL", "FlatAttnError", "flat_attn_fwd", "flat_attn_fwd_f32",
+           "flat_attn_unfused", "flat_attn_unfused_workspace_bytes", "flat_attn_status_string", "flat_attn_version",
+           "library_path", "load_library"]

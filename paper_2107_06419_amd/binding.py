@@ -1,0 +1,120 @@
+"""ctypes binding of include/flat_attn.h.  Same names as the C entry points; argument marshalling only.
+
+Tensors are torch CUDA (ROCm) tensors used purely as device buffers: the binding passes
+`data_ptr()` and the current HIP stream to the library and returns the C status code turned into
+an exception.  Nothing here computes.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+FLAT_MASK_NONE = 0
+FLAT_MASK_CAUSAL = 1
+FLAT_DTYPE_BF16 = 0
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libflat_attn.so")
+_lib = None
+
+
+class FlatAttnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{message} (status {status})")
+        self.status = status
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libflat_attn.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2107_06419_amd.build` (needs hipcc)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.flat_attn_fwd.restype = i
+    lib.flat_attn_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, vp]
+    lib.flat_attn_fwd_f32.restype = i
+    lib.flat_attn_fwd_f32.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, vp]
+    lib.flat_attn_unfused_workspace_bytes.restype = sz
+    lib.flat_attn_unfused_workspace_bytes.argtypes = [i, i, i, i, i]
+    lib.flat_attn_unfused.restype = i
+    lib.flat_attn_unfused.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, vp, sz, i, vp]
+    lib.flat_attn_status_string.restype = ctypes.c_char_p
+    lib.flat_attn_status_string.argtypes = [i]
+    lib.flat_attn_version.restype = i
+    lib.flat_attn_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def flat_attn_status_string(status: int) -> str:
+    return load_library().flat_attn_status_string(int(status)).decode()
+
+
+def flat_attn_version() -> int:
+    return int(load_library().flat_attn_version())
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise FlatAttnError(status, flat_attn_status_string(status))
+
+
+def _stream_handle(stream) -> int:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _dev_args(dtype, *tensors):
+    shape = tensors[0].shape
+    if len(shape) != 4:
+        raise ValueError("expected [B, H, N, d] tensors")
+    for t in tensors:
+        if not t.is_cuda:
+            raise ValueError("tensors must live on the GPU")
+        if t.dtype != dtype:
+            raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
+        if t.shape != shape or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous and share one [B, H, N, d] shape")
+    return tuple(int(s) for s in shape)
+
+
+def flat_attn_fwd(Q, K, V, O, scale: float, mask_kind: int = FLAT_MASK_NONE, stream=None) -> None:
+    """Fused attention, bf16 [B,H,N,d] device tensors; O is overwritten. Enqueues on `stream`."""
+    import torch
+    B, H, N, d = _dev_args(torch.bfloat16, Q, K, V, O)
+    _check(load_library().flat_attn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
+                                        float(scale), int(mask_kind), _stream_handle(stream)))
+
+
+def flat_attn_fwd_f32(Q, K, V, O, scale: float, mask_kind: int = FLAT_MASK_NONE, stream=None) -> None:
+    """Fused attention in fp32, float32 [B,H,N,d] device tensors."""
+    import torch
+    B, H, N, d = _dev_args(torch.float32, Q, K, V, O)
+    _check(load_library().flat_attn_fwd_f32(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
+                                            float(scale), int(mask_kind), _stream_handle(stream)))
+
+
+def flat_attn_unfused_workspace_bytes(B: int, H: int, N: int, d: int, dtype: int = FLAT_DTYPE_BF16) -> int:
+    return int(load_library().flat_attn_unfused_workspace_bytes(int(B), int(H), int(N), int(d), int(dtype)))
+
+
+def flat_attn_unfused(Q, K, V, O, scale: float, mask_kind: int, workspace, stream=None) -> None:
+    """Unfused baseline; `workspace` is a device tensor of at least flat_attn_unfused_workspace_bytes() bytes."""
+    import torch
+    B, H, N, d = _dev_args(torch.bfloat16, Q, K, V, O)
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load_library().flat_attn_unfused(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
+                                            float(scale), int(mask_kind), workspace.data_ptr(), nbytes,
+                                            FLAT_DTYPE_BF16, _stream_handle(stream)))

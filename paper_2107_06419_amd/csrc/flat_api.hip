@@ -1,0 +1,107 @@
+// C ABI of the attention library (see include/flat_attn.h for the contract).
+// Every argument check below runs before the first HIP call, so a host without a GPU can
+// exercise the error paths.
+#include "../../include/flat_attn.h"
+
+#include <math.h>
+#include <stdint.h>
+
+#include "flat_launch.hpp"
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool overlaps(const void* a, size_t abytes, const void* b, size_t bbytes) {
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + bbytes && b0 < a0 + abytes;
+}
+
+// Shape / pointer checks shared by all entry points.  `elem` = bytes per tensor element.
+int check_common(const void* Q, const void* K, const void* V, const void* O, int B, int H, int N, int d, float scale,
+                 int mask_kind, size_t elem) {
+    if (!Q || !K || !V || !O) return FLAT_ERR_NULL;
+    if (B <= 0 || H <= 0 || N <= 0) return FLAT_ERR_SHAPE;
+    if (d != 64 && d != 128) return FLAT_ERR_UNSUPPORTED;
+    if (mask_kind != FLAT_MASK_NONE && mask_kind != FLAT_MASK_CAUSAL) return FLAT_ERR_UNSUPPORTED;
+    if (!(scale >= 0.0f) || isinf(scale)) return FLAT_ERR_UNSUPPORTED;  // also rejects NaN
+    // B*H must fit the grid; B*H*N*d*elem and B*H*N*N*4 must fit 63 bits
+    const long long BH = (long long)B * H;
+    if (BH > 0x7fffffffLL / ((N + 127) / 128)) return FLAT_ERR_SHAPE;
+    const unsigned __int128 tensor = (unsigned __int128)BH * (unsigned)N * (unsigned)d * elem;
+    const unsigned __int128 square = (unsigned __int128)BH * (unsigned)N * (unsigned)N * 4u;
+    const unsigned __int128 lim = (unsigned __int128)1 << 62;
+    if (tensor >= lim || square >= lim) return FLAT_ERR_SHAPE;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return FLAT_ERR_ALIGN;
+    const size_t bytes = (size_t)tensor;
+    if (overlaps(O, bytes, Q, bytes) || overlaps(O, bytes, K, bytes) || overlaps(O, bytes, V, bytes)) return FLAT_ERR_ALIAS;
+    return FLAT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int flat_attn_fwd(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
+                  int mask_kind, void* stream) {
+    const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 2);
+    if (rc != FLAT_OK) return rc;
+    const hipError_t e = flat::launch_fwd_bf16(Q, K, V, O, B * H, N, d, scale, mask_kind == FLAT_MASK_CAUSAL,
+                                               static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
+}
+
+int flat_attn_fwd_f32(const float* Q, const float* K, const float* V, float* O, int B, int H, int N, int d, float scale,
+                      int mask_kind, void* stream) {
+    const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 4);
+    if (rc != FLAT_OK) return rc;
+    const hipError_t e = flat::launch_fwd_f32(Q, K, V, O, B * H, N, d, scale, mask_kind == FLAT_MASK_CAUSAL,
+                                              static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
+}
+
+size_t flat_attn_unfused_workspace_bytes(int B, int H, int N, int d, int dtype) {
+    if (B <= 0 || H <= 0 || N <= 0 || (d != 64 && d != 128) || dtype != FLAT_DTYPE_BF16) return 0;
+    const unsigned __int128 square = (unsigned __int128)B * (unsigned)H * (unsigned)N * (unsigned)N * 4u;
+    if (square >= ((unsigned __int128)1 << 62)) return 0;
+    return (size_t)square;
+}
+
+int flat_attn_unfused(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
+                      int mask_kind, void* workspace, size_t workspace_bytes, int dtype, void* stream) {
+    if (dtype != FLAT_DTYPE_BF16) return FLAT_ERR_UNSUPPORTED;
+    const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 2);
+    if (rc != FLAT_OK) return rc;
+    if (!workspace) return FLAT_ERR_NULL;
+    if (!aligned16(workspace)) return FLAT_ERR_ALIGN;
+    if ((long long)B * H > 65535) return FLAT_ERR_SHAPE;                       // grid z/y limit of the GEMM launches
+    if ((unsigned long long)B * H * N > 0x7fffffffULL) return FLAT_ERR_SHAPE;  // one workgroup per row in the softmax
+    const size_t need = flat_attn_unfused_workspace_bytes(B, H, N, d, dtype);
+    if (need == 0) return FLAT_ERR_SHAPE;
+    if (workspace_bytes < need) return FLAT_ERR_WORKSPACE;
+    const size_t tbytes = (size_t)B * H * N * d * 2;
+    if (overlaps(workspace, need, Q, tbytes) || overlaps(workspace, need, K, tbytes) || overlaps(workspace, need, V, tbytes) ||
+        overlaps(workspace, need, O, tbytes))
+        return FLAT_ERR_ALIAS;
+    const hipError_t e = flat::launch_unfused_bf16(Q, K, V, O, B * H, N, d, scale, mask_kind == FLAT_MASK_CAUSAL,
+                                                   static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
+}
+
+const char* flat_attn_status_string(int status) {
+    switch (status) {
+        case FLAT_OK: return "FLAT_OK";
+        case FLAT_ERR_NULL: return "FLAT_ERR_NULL: a required pointer is NULL";
+        case FLAT_ERR_SHAPE: return "FLAT_ERR_SHAPE: B, H or N not positive, or the problem is too large to index";
+        case FLAT_ERR_UNSUPPORTED: return "FLAT_ERR_UNSUPPORTED: d must be 64 or 128, mask_kind 0 or 1, scale finite and >= 0";
+        case FLAT_ERR_ALIGN: return "FLAT_ERR_ALIGN: pointers must be 16-byte aligned";
+        case FLAT_ERR_WORKSPACE: return "FLAT_ERR_WORKSPACE: workspace smaller than flat_attn_unfused_workspace_bytes()";
+        case FLAT_ERR_HIP: return "FLAT_ERR_HIP: the HIP runtime refused a launch";
+        case FLAT_ERR_ALIAS: return "FLAT_ERR_ALIAS: output or workspace overlaps another buffer";
+        default: return "unknown flat_status";
+    }
+}
+
+int flat_attn_version(void) { return 100; }
+
+}  // extern "C"

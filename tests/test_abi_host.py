@@ -1,0 +1,79 @@
+"""Host-side checks of the C-ABI library: it loads without a GPU, exports every declared symbol,
+and rejects bad arguments before touching the HIP runtime."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2107_06419_amd as fa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "flat_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(flat_attn_\w+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    for must in ("flat_attn_fwd", "flat_attn_fwd_f32", "flat_attn_unfused", "flat_attn_unfused_workspace_bytes",
+                 "flat_attn_status_string", "flat_attn_version"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(fa.library_path()):
+        pytest.fail(f"{fa.library_path()} not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = ctypes.CDLL(fa.library_path())
+    for name in declared_functions():
+        assert hasattr(lib, name), f"libflat_attn.so does not export {name}"
+
+
+def test_binding_has_the_same_names():
+    for name in declared_functions():
+        assert hasattr(fa, name), f"python binding lacks {name}"
+
+
+def test_version_and_status_strings():
+    assert fa.flat_attn_version() >= 100
+    for code in range(0, -8, -1):
+        s = fa.flat_attn_status_string(code)
+        assert s and "unknown" not in s
+    assert "unknown" in fa.flat_attn_status_string(-99)
+
+
+def test_validation_happens_before_any_gpu_work():
+    lib = fa.load_library()
+    ok = (0x1000, 0x2000000, 0x4000000, 0x6000000)  # fake, aligned, far apart: never dereferenced on these paths
+
+    def fwd(Q=ok[0], K=ok[1], V=ok[2], O=ok[3], B=1, H=1, N=8, d=64, scale=1.0, mask=0):
+        return lib.flat_attn_fwd(Q, K, V, O, B, H, N, d, scale, mask, None)
+
+    assert fwd(Q=None) == -1 and fwd(K=None) == -1 and fwd(V=None) == -1 and fwd(O=None) == -1
+    assert fwd(B=0) == -2 and fwd(H=-1) == -2 and fwd(N=0) == -2
+    assert fwd(d=32) == -3 and fwd(d=96) == -3 and fwd(mask=2) == -3 and fwd(mask=-1) == -3
+    assert fwd(scale=-0.5) == -3 and fwd(scale=float("inf")) == -3 and fwd(scale=float("nan")) == -3
+    assert fwd(Q=ok[0] + 8) == -4 and fwd(O=ok[3] + 2) == -4
+    assert fwd(O=ok[0]) == -7 and fwd(O=ok[1] + 16) == -7
+    assert fwd(B=1 << 20, H=1 << 20, N=1 << 20) == -2           # index overflow
+    assert lib.flat_attn_fwd_f32(ok[0], ok[1], ok[2], ok[3], 1, 1, 8, 48, 1.0, 0, None) == -3
+
+    assert fa.flat_attn_unfused_workspace_bytes(1, 16, 16384, 64) == 16 * 16384 * 16384 * 4
+    assert fa.flat_attn_unfused_workspace_bytes(1, 8, 65536, 64) == 8 * 65536 * 65536 * 4
+    assert fa.flat_attn_unfused_workspace_bytes(1, 1, 8, 96) == 0
+
+    def unf(ws=0x8000000, ws_bytes=1 << 20, dtype=0, **kw):
+        a = dict(Q=ok[0], K=ok[1], V=ok[2], O=ok[3], B=1, H=1, N=8, d=64, scale=1.0, mask=0)
+        a.update(kw)
+        return lib.flat_attn_unfused(a["Q"], a["K"], a["V"], a["O"], a["B"], a["H"], a["N"], a["d"], a["scale"], a["mask"],
+                                     ws, ws_bytes, dtype, None)
+
+    assert unf(ws=None) == -1
+    assert unf(ws_bytes=8 * 8 * 4 - 1) == -5
+    assert unf(dtype=1) == -3
+    assert unf(ws=0x8000004) == -4
+    assert unf(ws=ok[3]) == -7
+    assert unf(N=0) == -2

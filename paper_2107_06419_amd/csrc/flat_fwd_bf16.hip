@@ -20,17 +20,27 @@
 
 namespace flat {
 
+// LDS tile layout.  Rows are stored unpadded (ROWB = 2 D bytes) because tiles arrive by
+// global_load_lds_dwordx4, which writes the 64 lanes of a wavefront to 1024 contiguous LDS bytes
+// (lane l at base + 16 l).  Bank conflicts are avoided instead by an XOR swizzle of the 16-byte
+// chunk index within a row: chunk c of row r lives in slot c ^ swz(r).  The LDS serves 256 bytes
+// per clock: a ds_read_b128 touches 16 rows at one chunk index per clock, a ds_read_b64_tr_b16
+// touches 4 rows x 64 bytes; swz() is chosen so that both patterns hit every bank once.
 template <int D>
 struct Bf16Cfg {
     static constexpr int BC = 64;                     // keys per tile
-    static constexpr int KSTRIDE = D * 2 + 16;        // LDS bytes per K row: conflict-free ds_read_b128 of 16 rows
-    static constexpr int VSTRIDE = D * 2 + 64;        // LDS bytes per V row: conflict-free ds_read_b64_tr_b16 of 4 rows
-    static constexpr int KBYTES = BC * KSTRIDE;
-    static constexpr int VBYTES = BC * VSTRIDE;
+    static constexpr int ROWB = D * 2;                // bytes per row
+    static constexpr int CHUNKS = ROWB / 16;          // 16-byte chunks per row
+    static constexpr int KBYTES = BC * ROWB;
+    static constexpr int VBYTES = BC * ROWB;
     static constexpr int STAGE = KBYTES + VBYTES;
-    static constexpr int CHUNKS = D * 2 / 16;         // 16-byte chunks per row
-    static constexpr int LOADS = BC * CHUNKS / 256;   // chunks per thread per tensor per tile
+    static constexpr int ROWS_PER_LOAD = 1024 / ROWB; // rows covered by one wave-wide 16-byte-per-lane load
+    static constexpr int LOADS = BC / ROWS_PER_LOAD / 4;  // such loads per wavefront per tensor per tile
     static constexpr int LDS_BYTES = 2 * STAGE;
+    __device__ static __forceinline__ int swz(int r) {
+        if (D == 64) return (((r >> 1) & 1) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1);  // 128-byte rows: 2 rows per 256 B
+        return ((r & 3) << 2) | ((r >> 2) & 3);                                              // 256-byte rows
+    }
 };
 
 template <int D, int QB, bool CAUSAL>
@@ -84,142 +94,140 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
     if (CAUSAL) kv_len = min(N, qt * BR + BR);
     const int n_tiles = (kv_len + BC - 1) / BC;
 
-    // global -> register -> LDS staging of one K tile and one V tile
-    uint4v kreg[C::LOADS], vreg[C::LOADS];
-    auto gload = [&](int tile) {
-#pragma unroll
-        for (int i = 0; i < C::LOADS; ++i) {
-            const int ch = tid + 256 * i;
-            const int row = ch / C::CHUNKS, col = ch % C::CHUNKS;
-            const int key = tile * BC + row;
-            uint4v zk = {0, 0, 0, 0}, zv = {0, 0, 0, 0};
-            if (key < N) {
-                const size_t off = (size_t)key * (D * 2) + col * 16;
-                zk = *(const uint4v*)(Kh + off);
-                zv = *(const uint4v*)(Vh + off);
-            }
-            kreg[i] = zk;
-            vreg[i] = zv;
-        }
-    };
-    auto lstore = [&](int stage) {
+    // global -> LDS copy of one K tile and one V tile, no registers in between.  Wave w issues load
+    // i for the 1024-byte LDS block (4 i + w); lane l fills slot (l % CHUNKS) of row (l / CHUNKS) of
+    // that block, so it fetches the chunk whose swizzled position that is.  Keys beyond N are clamped
+    // to the last key: their logits are masked and their (finite) values meet a zero probability.
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    const int ld_row = lane / C::CHUNKS;
+    auto issue_tile_loads = [&](int tile, int stage) {
         char* Kb = smem + stage * C::STAGE;
         char* Vb = Kb + C::KBYTES;
 #pragma unroll
         for (int i = 0; i < C::LOADS; ++i) {
-            const int ch = tid + 256 * i;
-            const int row = ch / C::CHUNKS, col = ch % C::CHUNKS;
-            *(uint4v*)(Kb + row * C::KSTRIDE + col * 16) = kreg[i];
-            *(uint4v*)(Vb + row * C::VSTRIDE + col * 16) = vreg[i];
+            const int blk = 4 * i + wave;
+            const int row = blk * C::ROWS_PER_LOAD + ld_row;
+            const int chunk = (lane % C::CHUNKS) ^ C::swz(row);
+            const int key = min(tile * BC + row, N - 1);
+            const size_t off = (size_t)key * C::ROWB + chunk * 16;
+            __builtin_amdgcn_global_load_lds((gptr_t)(Kh + off), (lptr_t)(Kb + blk * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(Vh + off), (lptr_t)(Vb + blk * 1024), 16, 0, 0);
         }
     };
+    auto wait_tile_loads = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
-    // per-lane LDS offsets of the MFMA operand reads
-    const int k_lane_off = l32 * C::KSTRIDE + half * 16;
+    // per-lane LDS byte offsets of the MFMA operand reads (row part + swizzled chunk), one per
+    // compile-time chunk index
+    int koff[DS];
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) koff[ds] = l32 * C::ROWB + (((2 * ds + half) ^ C::swz(l32)) << 4);
     const int i16 = lane & 15, g16 = lane >> 4;
-    const int v_lane_off = (4 * (g16 >> 1) + (i16 >> 2)) * C::VSTRIDE + (16 * (g16 & 1) + 4 * (i16 & 3)) * 2;
+    int voff[DB][2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int hi = 0; hi < 2; ++hi) {
+            const int r = 8 * hi + 4 * (g16 >> 1) + (i16 >> 2);             // row within a 16-key step
+            const int ch = 4 * db + 2 * (g16 & 1) + ((i16 >> 1) & 1);      // 16-byte chunk holding this lane's 4 columns
+            voff[db][hi] = r * C::ROWB + ((ch ^ C::swz(r)) << 4) + (i16 & 1) * 8;
+        }
     const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
 
+    // One tile = 64 keys, processed as two blocks of 32 keys so that only a 32 x QW logit block and its
+    // probabilities are live at a time.
     auto compute_tile = [&](int stage, int jbase, bool masked) {
         const char* Kb = smem + stage * C::STAGE;
         const char* Vb = Kb + C::KBYTES;
-        // ---- Logit: S^T[key, query]
-        floatx16 s[QB][2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
+            // ---- Logit: S^T[key, query] for keys jbase + 32 kb .. + 31
+            floatx16 s[QB];
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[qb][kb][r] = 0.f;
+                for (int r = 0; r < 16; ++r) s[qb][r] = 0.f;
 #pragma unroll
             for (int ds = 0; ds < DS; ++ds) {
-                const bf16x8 kf = *(const bf16x8*)(Kb + kb * 32 * C::KSTRIDE + k_lane_off + ds * 32);
+                const bf16x8 kf = *(const bf16x8*)(Kb + kb * 32 * C::ROWB + koff[ds]);
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb) s[qb][kb] = mfma_bf16_32x32x16(kf, qf[qb][ds], s[qb][kb]);
+                for (int qb = 0; qb < QB; ++qb) s[qb] = mfma_bf16_32x32x16(kf, qf[qb][ds], s[qb]);
             }
-        }
-        // ---- row softmax with running max / sum; a lane owns query (l32) of each 32-row block
-        uint32_t p[QB][2][8];
+            // ---- row softmax with running max / sum; a lane owns query (l32) of each 32-row block
+            uint32_t p[QB][8];
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            uint32_t okmask[2] = {0xffffffffu, 0xffffffffu};
-            if (masked) {
-                const int qidx = q0w + 32 * qb + l32;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    uint32_t mk = 0;
+            for (int qb = 0; qb < QB; ++qb) {
+                uint32_t okmask = 0xffffffffu;
+                if (masked) {
+                    const int qidx = q0w + 32 * qb + l32;
+                    okmask = 0;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int key = jbase + 32 * kb + acc_row(r, half);
                         const bool ok = key < N && (!CAUSAL || key <= qidx);
-                        mk |= ok ? (1u << r) : 0u;
-                        s[qb][kb][r] = ok ? s[qb][kb][r] : -INFINITY;
+                        okmask |= ok ? (1u << r) : 0u;
+                        s[qb][r] = ok ? s[qb][r] : -INFINITY;
                     }
-                    okmask[kb] = mk;
                 }
-            }
-            float mx = s[qb][0][0];
+                float mx = s[qb][0];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+                for (int r = 1; r < 16; ++r) mx = __builtin_fmaxf(mx, s[qb][r]);
+                mx = halves_max(mx);
+                // mx * c is NaN only if c == 0 and the block is fully masked; fmaxf then keeps m
+                const float m_new = __builtin_fmaxf(m[qb], mx * c);
+                if (__builtin_amdgcn_ballot_w64(m_new != m[qb]) != 0) {
+                    const float alpha = __builtin_amdgcn_exp2f(m[qb] - m_new);
+                    lsum[qb] *= alpha;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mx = __builtin_fmaxf(mx, s[qb][kb][r]);
-            mx = halves_max(mx);
-            const float m_new = __builtin_fmaxf(m[qb], mx * c);
-            if (__builtin_amdgcn_ballot_w64(m_new != m[qb]) != 0) {
-                const float alpha = __builtin_amdgcn_exp2f(m[qb] - m_new);
-                lsum[qb] *= alpha;
+                    for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha;
-                m[qb] = m_new;
-            }
-            float ls = lsum[qb];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+                        for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha;
+                    m[qb] = m_new;
+                }
+                float ls = lsum[qb];
 #pragma unroll
                 for (int r = 0; r < 16; r += 2) {
-                    float x0 = __builtin_fmaf(s[qb][kb][r], c, -m_new);
-                    float x1 = __builtin_fmaf(s[qb][kb][r + 1], c, -m_new);
+                    float x0 = __builtin_fmaf(s[qb][r], c, -m_new);
+                    float x1 = __builtin_fmaf(s[qb][r + 1], c, -m_new);
                     if (masked) {
-                        x0 = (okmask[kb] >> r) & 1u ? x0 : -INFINITY;
-                        x1 = (okmask[kb] >> (r + 1)) & 1u ? x1 : -INFINITY;
+                        x0 = (okmask >> r) & 1u ? x0 : -INFINITY;
+                        x1 = (okmask >> (r + 1)) & 1u ? x1 : -INFINITY;
                     }
                     const float p0 = __builtin_amdgcn_exp2f(x0);
                     const float p1 = __builtin_amdgcn_exp2f(x1);
                     const uint32_t pk = pack_bf16(p0, p1);
-                    p[qb][kb][r >> 1] = pk;
+                    p[qb][r >> 1] = pk;
                     // row sum of the ROUNDED probabilities, so that sum and the Attend operand agree
                     ls = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, ls, false);
                 }
-            lsum[qb] = ls;
-        }
-        // ---- Attend: O^T[dcol, query] += V^T[dcol, key] P^T[key, query]
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+                lsum[qb] = ls;
+            }
+            // ---- Attend: O^T[dcol, query] += V^T[dcol, key] P^T[key, query]
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                const char* vrow = Vb + (kb * 32 + t * 16) * C::VSTRIDE + v_lane_off;
+                const char* vrow = Vb + (kb * 32 + t * 16) * C::ROWB;  // swz() only looks at row bits below 16
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    const bf16x4 lo = lds_read_tr16(vrow + db * 64);
-                    const bf16x4 hi = lds_read_tr16(vrow + db * 64 + 8 * C::VSTRIDE);
+                    const bf16x4 lo = lds_read_tr16(vrow + voff[db][0]);
+                    const bf16x4 hi = lds_read_tr16(vrow + voff[db][1]);
                     const bf16x8 vf = concat(lo, hi);
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb) {
-                        uint4v pw = {p[qb][kb][4 * t], p[qb][kb][4 * t + 1], p[qb][kb][4 * t + 2], p[qb][kb][4 * t + 3]};
+                        uint4v pw = {p[qb][4 * t], p[qb][4 * t + 1], p[qb][4 * t + 2], p[qb][4 * t + 3]};
                         oacc[qb][db] = mfma_bf16_32x32x16(vf, __builtin_bit_cast(bf16x8, pw), oacc[qb][db]);
                     }
                 }
             }
+        }
     };
 
-    gload(0);
-    lstore(0);
+    issue_tile_loads(0, 0);
+    wait_tile_loads();
     __syncthreads();
+#pragma unroll 1
     for (int j = 0; j < n_tiles; ++j) {
         const bool more = j + 1 < n_tiles;
-        if (more) gload(j + 1);
+        if (more) issue_tile_loads(j + 1, (j + 1) & 1);  // that stage was last read before the previous barrier
         const int jbase = j * BC;
         const bool active = !CAUSAL || jbase <= q0w + QW - 1;
         if (active) {
@@ -229,7 +237,7 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
             else
                 compute_tile(j & 1, jbase, false);
         }
-        if (more) lstore((j + 1) & 1);
+        wait_tile_loads();
         __syncthreads();
     }
 

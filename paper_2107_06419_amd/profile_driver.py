@@ -1,0 +1,55 @@
+"""Workload driver for rocprofv3 runs:  rocprofv3 <options> -- python3 -m paper_2107_06419_amd.profile_driver ...
+
+Launches, in this order and each `--reps` times on one workload: the fused kernel, optionally the
+three unfused kernels, and a plain device-to-device copy of a known size (the calibration kernel
+for byte counters such as FETCH_SIZE / WRITE_SIZE).
+"""
+import argparse
+import sys
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="cfg2_long_16k")
+    ap.add_argument("--reps", type=int, default=3)
+    ap.add_argument("--unfused", action="store_true")
+    ap.add_argument("--copy-mib", type=int, default=1024, help="size of the calibration copy (MiB read + MiB written)")
+    args = ap.parse_args()
+
+    import numpy as np
+    import torch
+
+    import paper_2107_06419_amd as fa
+    from paper_2107_06419_amd import synth
+
+    w = synth.WORKLOADS[args.workload]
+    q, k, v = synth.make_qkv(w)
+
+    def dev(x):
+        return torch.from_numpy(synth.f32_to_bf16_bits(x).reshape(x.shape).view(np.int16)).cuda().view(torch.bfloat16)
+
+    dq, dk, dv = dev(q), dev(k), dev(v)
+    out = torch.empty_like(dq)
+    for _ in range(args.reps):
+        fa.flat_attn_fwd(dq, dk, dv, out, w.scale, w.mask)
+    torch.cuda.synchronize()
+    if args.unfused:
+        ws = torch.empty(fa.flat_attn_unfused_workspace_bytes(w.B, w.H, w.N, w.d) // 4, dtype=torch.float32, device="cuda")
+        for _ in range(args.reps):
+            fa.flat_attn_unfused(dq, dk, dv, out, w.scale, w.mask, ws)
+        torch.cuda.synchronize()
+        del ws
+    if args.copy_mib > 0:
+        n = args.copy_mib * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(args.reps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+    print("profile_driver done", args.workload, flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -3,22 +3,32 @@
 // Dataflow (paper sections 4-5: fused Logit-softmax-Attend with a shared outer loop over batch,
 // head and blocks of query rows, the two inner loops interleaved):
 //   one workgroup = one (batch, head, block of BR query rows); its 4 wavefronts own QW = BR/4 rows
-//   each.  The key/value sequence is streamed in tiles of BC = 64 keys through LDS (two stages, the
-//   paper's double-buffered operand tiles).  Per tile a wavefront computes
-//       S^T = K_tile Q^T           (Logit, MFMA 32x32x16 bf16; the transposed product is chosen so
+//   each.  The key/value sequence is streamed in tiles of 64 keys through a ring of LDS stages
+//   (the paper's double-buffered operand tiles, deepened to hide HBM/L2 latency).  Each tile is
+//   consumed as two blocks of 32 keys; per block a wavefront computes
+//       S^T = K_blk Q^T            (Logit, MFMA 32x32x16 bf16; the transposed product is chosen so
 //                                   that a lane owns ONE query column: row max / row sum are then
 //                                   in-lane reductions plus one exchange between wave halves)
-//       P   = exp2(c S - m)        (row softmax numerator with running max m, fp32, then bf16 RNE)
-//       O^T += V_tile^T P^T        (Attend; the accumulator layout of S^T is already the B-operand
+//       P   = exp2(c S - m)        (row softmax numerator against a reference max m, fp32 -> bf16 RNE)
+//       O^T += V_blk^T P^T         (Attend; the accumulator layout of S^T is already the B-operand
 //                                   layout of this product, so P never leaves registers;
 //                                   V^T operands come from ds_read_b64_tr_b16 on row-major V)
 // and only Q, K, V are read and O written: the N x N intermediate never exists off-chip.
 // Unlike the paper's row-granularity tile, which keeps a whole R x N logit slab on chip, the row
 // max and sum are carried as running values, so on-chip state is independent of N.
+//
+// Reference max.  softmax is invariant to the constant subtracted per row, so m need not be the
+// exact running maximum.  It starts as the (scaled) logit of key 0, which every query sees, so the
+// row sum is at least 1 and can never underflow; it is raised (and O, l rescaled) only when a
+// block's maximum exceeds it by more than kRescaleSlack, which keeps every exponent
+// <= 2^kRescaleSlack.  For typical data that happens in the first blocks only, so the steady-state
+// loop carries a compare but no rescale.
 #include "flat_common.hpp"
 #include "flat_launch.hpp"
 
 namespace flat {
+
+constexpr float kRescaleSlack = 8.0f;  // log2 units
 
 // LDS tile layout.  Rows are stored unpadded (ROWB = 2 D bytes) because tiles arrive by
 // global_load_lds_dwordx4, which writes the 64 lanes of a wavefront to 1024 contiguous LDS bytes
@@ -26,7 +36,7 @@ namespace flat {
 // chunk index within a row: chunk c of row r lives in slot c ^ swz(r).  The LDS serves 256 bytes
 // per clock: a ds_read_b128 touches 16 rows at one chunk index per clock, a ds_read_b64_tr_b16
 // touches 4 rows x 64 bytes; swz() is chosen so that both patterns hit every bank once.
-template <int D>
+template <int D, int STAGES>
 struct Bf16Cfg {
     static constexpr int BC = 64;                     // keys per tile
     static constexpr int ROWB = D * 2;                // bytes per row
@@ -36,19 +46,36 @@ struct Bf16Cfg {
     static constexpr int STAGE = KBYTES + VBYTES;
     static constexpr int ROWS_PER_LOAD = 1024 / ROWB; // rows covered by one wave-wide 16-byte-per-lane load
     static constexpr int LOADS = BC / ROWS_PER_LOAD / 4;  // such loads per wavefront per tensor per tile
-    static constexpr int LDS_BYTES = 2 * STAGE;
+    static constexpr int LDS_BYTES = STAGES * STAGE;
     __device__ static __forceinline__ int swz(int r) {
         if (D == 64) return (((r >> 1) & 1) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1);  // 128-byte rows: 2 rows per 256 B
         return ((r & 3) << 2) | ((r >> 2) & 3);                                              // 256-byte rows
     }
 };
 
-template <int D, int QB, bool CAUSAL>
+// One wave-wide global -> LDS copy, 16 bytes per lane: lane l's bytes land at lds_base + 16 l.
+// Issued as inline asm so that the compiler does not serialise later LDS reads of OTHER stages
+// behind it; completion is awaited explicitly with wait_vm<n>() before the stage is published by
+// a barrier.  lds_base must be wave-uniform.
+__device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(gbase) : "memory");
+}
+// s_waitcnt vmcnt(CNT) with the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4, lgkmcnt 11:8).  Emitted through the builtin so that the compiler's own wait bookkeeping
+// sees it.
+template <int CNT>
+__device__ __forceinline__ void wait_vm() {
+    static_assert(CNT >= 0 && CNT < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((CNT & 15) | ((CNT >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+template <int D, int QB, int STAGES, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                           const bf16* __restrict__ V, bf16* __restrict__ O, int N,
                                                           int n_qtiles, int n_blocks, int blocks_per_xcd, float c) {
-    using C = Bf16Cfg<D>;
+    using C = Bf16Cfg<D, STAGES>;
     constexpr int QW = 32 * QB, BR = 4 * QW, BC = C::BC, DS = D / 16, DB = D / 32;
+    constexpr int LOADS_PER_TILE = 2 * C::LOADS;  // DMA instructions per wavefront per tile (K and V)
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int logical = xcd_logical_block(blockIdx.x, blocks_per_xcd);
@@ -78,12 +105,33 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
         }
     }
 
+    // reference max of each row = c * (q . k_0), from the fragments already in registers
+    float m[QB];
+    {
+        float k0[DS][8];
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) {
+            const uint4v kv = *(const uint4v*)(Kh + ds * 32 + half * 16);
+            const bf16x8 kb8 = __builtin_bit_cast(bf16x8, kv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) k0[ds][e] = (float)kb8[e];
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            float dot = 0.f;
+#pragma unroll
+            for (int ds = 0; ds < DS; ++ds)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot = __builtin_fmaf((float)qf[qb][ds][e], k0[ds][e], dot);
+            m[qb] = halves_sum(dot) * c;
+        }
+    }
+
     floatx16 oacc[QB][DB];
-    float m[QB], lsum[QB];
+    float lsum[QB][2];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        m[qb] = -INFINITY;
-        lsum[qb] = 0.f;
+        lsum[qb][0] = lsum[qb][1] = 0.f;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -94,28 +142,28 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
     if (CAUSAL) kv_len = min(N, qt * BR + BR);
     const int n_tiles = (kv_len + BC - 1) / BC;
 
-    // global -> LDS copy of one K tile and one V tile, no registers in between.  Wave w issues load
-    // i for the 1024-byte LDS block (4 i + w); lane l fills slot (l % CHUNKS) of row (l / CHUNKS) of
-    // that block, so it fetches the chunk whose swizzled position that is.  Keys beyond N are clamped
-    // to the last key: their logits are masked and their (finite) values meet a zero probability.
-    typedef const __attribute__((address_space(1))) void* gptr_t;
-    typedef __attribute__((address_space(3))) void* lptr_t;
-    const int ld_row = lane / C::CHUNKS;
-    auto issue_tile_loads = [&](int tile, int stage) {
-        char* Kb = smem + stage * C::STAGE;
-        char* Vb = Kb + C::KBYTES;
+    // ---- global -> LDS streaming.  Wave w issues load i of a tile for the 1024-byte LDS block
+    // (4 i + w); lane l fills slot (l % CHUNKS) of row (l / CHUNKS) of that block, so it fetches
+    // the chunk whose swizzled position that is.  Keys beyond N are clamped to the last key: their
+    // logits are masked and their (finite) values meet a zero probability.
+    const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
+    int ld_row[C::LOADS], ld_chunk_off[C::LOADS];
+#pragma unroll
+    for (int i = 0; i < C::LOADS; ++i) {
+        ld_row[i] = (4 * i + wave) * C::ROWS_PER_LOAD + lane / C::CHUNKS;
+        ld_chunk_off[i] = ((lane % C::CHUNKS) ^ C::swz(ld_row[i])) * 16;
+    }
+    auto issue_tile_loads = [&](int tile) {
+        const uint32_t stage_base = smem_base + (uint32_t)(tile % STAGES) * C::STAGE;
 #pragma unroll
         for (int i = 0; i < C::LOADS; ++i) {
-            const int blk = 4 * i + wave;
-            const int row = blk * C::ROWS_PER_LOAD + ld_row;
-            const int chunk = (lane % C::CHUNKS) ^ C::swz(row);
-            const int key = min(tile * BC + row, N - 1);
-            const size_t off = (size_t)key * C::ROWB + chunk * 16;
-            __builtin_amdgcn_global_load_lds((gptr_t)(Kh + off), (lptr_t)(Kb + blk * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(Vh + off), (lptr_t)(Vb + blk * 1024), 16, 0, 0);
+            const int key = min(tile * BC + ld_row[i], N - 1);
+            const uint32_t voff = (uint32_t)key * C::ROWB + ld_chunk_off[i];
+            const uint32_t lds_k = __builtin_amdgcn_readfirstlane(stage_base + (4 * i + wave) * 1024);
+            dma16(Kh, voff, lds_k);
+            dma16(Vh, voff, lds_k + C::KBYTES);
         }
     };
-    auto wait_tile_loads = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
     // per-lane LDS byte offsets of the MFMA operand reads (row part + swizzled chunk), one per
     // compile-time chunk index
@@ -128,123 +176,188 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int hi = 0; hi < 2; ++hi) {
-            const int r = 8 * hi + 4 * (g16 >> 1) + (i16 >> 2);             // row within a 16-key step
-            const int ch = 4 * db + 2 * (g16 & 1) + ((i16 >> 1) & 1);      // 16-byte chunk holding this lane's 4 columns
+            const int r = 8 * hi + 4 * (g16 >> 1) + (i16 >> 2);         // row within a 16-key step
+            const int ch = 4 * db + 2 * (g16 & 1) + ((i16 >> 1) & 1);  // 16-byte chunk holding this lane's 4 columns
             voff[db][hi] = r * C::ROWB + ((ch ^ C::swz(r)) << 4) + (i16 & 1) * 8;
         }
     const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
 
-    // One tile = 64 keys, processed as two blocks of 32 keys so that only a 32 x QW logit block and its
-    // probabilities are live at a time.
-    auto compute_tile = [&](int stage, int jbase, bool masked) {
-        const char* Kb = smem + stage * C::STAGE;
-        const char* Vb = Kb + C::KBYTES;
+    // ---- block = 32 keys.  front(): x = c S - m and the per-row maximum of x; back(): exponentials and Attend.
+    auto front = [&](const char* Kb, int kbase, bool masked, floatx16 (&x)[QB], float (&mx)[QB]) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            // ---- Logit: S^T[key, query] for keys jbase + 32 kb .. + 31
-            floatx16 s[QB];
+        for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
+            for (int r = 0; r < 16; ++r) x[qb][r] = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[qb][r] = 0.f;
+        for (int ds = 0; ds < DS; ++ds) {
+            const bf16x8 kf = *(const bf16x8*)(Kb + koff[ds]);
 #pragma unroll
-            for (int ds = 0; ds < DS; ++ds) {
-                const bf16x8 kf = *(const bf16x8*)(Kb + kb * 32 * C::ROWB + koff[ds]);
+            for (int qb = 0; qb < QB; ++qb) x[qb] = mfma_bf16_32x32x16(kf, qf[qb][ds], x[qb]);
+        }
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb) s[qb] = mfma_bf16_32x32x16(kf, qf[qb][ds], s[qb]);
+        for (int qb = 0; qb < QB; ++qb) {
+            const float mref = m[qb];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) x[qb][r] = __builtin_fmaf(x[qb][r], c, -mref);
+            if (masked) {
+                const int qidx = q0w + 32 * qb + l32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = kbase + acc_row(r, half);
+                    const bool ok = key < N && (!CAUSAL || key <= qidx);
+                    x[qb][r] = ok ? x[qb][r] : -INFINITY;  // exp2 -> probability exactly 0
+                }
             }
-            // ---- row softmax with running max / sum; a lane owns query (l32) of each 32-row block
-            uint32_t p[QB][8];
+            float a = __builtin_fmaxf(x[qb][0], x[qb][1]), b2 = __builtin_fmaxf(x[qb][8], x[qb][9]);
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                uint32_t okmask = 0xffffffffu;
-                if (masked) {
-                    const int qidx = q0w + 32 * qb + l32;
-                    okmask = 0;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = jbase + 32 * kb + acc_row(r, half);
-                        const bool ok = key < N && (!CAUSAL || key <= qidx);
-                        okmask |= ok ? (1u << r) : 0u;
-                        s[qb][r] = ok ? s[qb][r] : -INFINITY;
-                    }
-                }
-                float mx = s[qb][0];
-#pragma unroll
-                for (int r = 1; r < 16; ++r) mx = __builtin_fmaxf(mx, s[qb][r]);
-                mx = halves_max(mx);
-                // mx * c is NaN only if c == 0 and the block is fully masked; fmaxf then keeps m
-                const float m_new = __builtin_fmaxf(m[qb], mx * c);
-                if (__builtin_amdgcn_ballot_w64(m_new != m[qb]) != 0) {
-                    const float alpha = __builtin_amdgcn_exp2f(m[qb] - m_new);
-                    lsum[qb] *= alpha;
-#pragma unroll
-                    for (int db = 0; db < DB; ++db)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha;
-                    m[qb] = m_new;
-                }
-                float ls = lsum[qb];
-#pragma unroll
-                for (int r = 0; r < 16; r += 2) {
-                    float x0 = __builtin_fmaf(s[qb][r], c, -m_new);
-                    float x1 = __builtin_fmaf(s[qb][r + 1], c, -m_new);
-                    if (masked) {
-                        x0 = (okmask >> r) & 1u ? x0 : -INFINITY;
-                        x1 = (okmask >> (r + 1)) & 1u ? x1 : -INFINITY;
-                    }
-                    const float p0 = __builtin_amdgcn_exp2f(x0);
-                    const float p1 = __builtin_amdgcn_exp2f(x1);
-                    const uint32_t pk = pack_bf16(p0, p1);
-                    p[qb][r >> 1] = pk;
-                    // row sum of the ROUNDED probabilities, so that sum and the Attend operand agree
-                    ls = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, ls, false);
-                }
-                lsum[qb] = ls;
+            for (int r = 2; r < 8; r += 2) {
+                a = __builtin_fmaxf(a, __builtin_fmaxf(x[qb][r], x[qb][r + 1]));
+                b2 = __builtin_fmaxf(b2, __builtin_fmaxf(x[qb][r + 8], x[qb][r + 9]));
             }
-            // ---- Attend: O^T[dcol, query] += V^T[dcol, key] P^T[key, query]
+            mx[qb] = halves_max(__builtin_fmaxf(a, b2));
+        }
+    };
+    auto back = [&](const char* Vb, floatx16 (&x)[QB]) {
+        uint32_t p[QB][8];
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const char* vrow = Vb + (kb * 32 + t * 16) * C::ROWB;  // swz() only looks at row bits below 16
+        for (int qb = 0; qb < QB; ++qb) {
+            float l0 = lsum[qb][0], l1 = lsum[qb][1];
 #pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const bf16x4 lo = lds_read_tr16(vrow + voff[db][0]);
-                    const bf16x4 hi = lds_read_tr16(vrow + voff[db][1]);
-                    const bf16x8 vf = concat(lo, hi);
+            for (int r = 0; r < 16; r += 4) {
+                float e[4];
 #pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) {
-                        uint4v pw = {p[qb][4 * t], p[qb][4 * t + 1], p[qb][4 * t + 2], p[qb][4 * t + 3]};
-                        oacc[qb][db] = mfma_bf16_32x32x16(vf, __builtin_bit_cast(bf16x8, pw), oacc[qb][db]);
-                    }
+                for (int i = 0; i < 4; ++i) e[i] = __builtin_amdgcn_exp2f(x[qb][r + i]);
+                const uint32_t pk0 = pack_bf16(e[0], e[1]), pk1 = pack_bf16(e[2], e[3]);
+                p[qb][r >> 1] = pk0;
+                p[qb][(r >> 1) + 1] = pk1;
+                // row sum of the ROUNDED probabilities, so that the sum and the Attend operand agree
+                l0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0), ones, l0, false);
+                l1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1), ones, l1, false);
+            }
+            lsum[qb][0] = l0;
+            lsum[qb][1] = l1;
+        }
+        // Attend: O^T[dcol, query] += V^T[dcol, key] P^T[key, query]
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const char* vrow = Vb + t * 16 * C::ROWB;  // swz() only looks at row bits below 16
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const bf16x4 lo = lds_read_tr16(vrow + voff[db][0]);
+                const bf16x4 hi = lds_read_tr16(vrow + voff[db][1]);
+                const bf16x8 vf = concat(lo, hi);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    uint4v pw = {p[qb][4 * t], p[qb][4 * t + 1], p[qb][4 * t + 2], p[qb][4 * t + 3]};
+                    oacc[qb][db] = mfma_bf16_32x32x16(vf, __builtin_bit_cast(bf16x8, pw), oacc[qb][db]);
                 }
             }
         }
     };
-
-    issue_tile_loads(0, 0);
-    wait_tile_loads();
-    __syncthreads();
-#pragma unroll 1
-    for (int j = 0; j < n_tiles; ++j) {
-        const bool more = j + 1 < n_tiles;
-        if (more) issue_tile_loads(j + 1, (j + 1) & 1);  // that stage was last read before the previous barrier
-        const int jbase = j * BC;
-        const bool active = !CAUSAL || jbase <= q0w + QW - 1;
-        if (active) {
-            const bool masked = (jbase + BC > N) || (CAUSAL && jbase + BC - 1 > q0w);
-            if (masked)
-                compute_tile(j & 1, jbase, true);
-            else
-                compute_tile(j & 1, jbase, false);
+    // Rare path: raise the reference max of every row whose block maximum lies above it, rescale O and l,
+    // and shift the block's exponents accordingly.
+    auto rescale = [&](floatx16 (&x)[QB], const float (&mx)[QB]) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float delta = __builtin_fmaxf(mx[qb], 0.f);
+            const float alpha = __builtin_amdgcn_exp2f(-delta);
+            m[qb] += delta;
+            lsum[qb][0] *= alpha;
+            lsum[qb][1] *= alpha;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) x[qb][r] -= delta;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(oacc[qb][db][r]) : "v"(alpha));
         }
-        wait_tile_loads();
-        __syncthreads();
+    };
+    auto needs_rescale = [&](const float (&mx)[QB]) {
+        bool need = false;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) need |= mx[qb] > kRescaleSlack;
+        return __builtin_amdgcn_ballot_w64(need) != 0;
+    };
+
+    // ---- prologue: fill STAGES-1 stages.  The full wait also retires the Q loads above, so that no
+    // wait on them is left inside the loops (it would drain the prefetch ring every iteration).
+#pragma unroll
+    for (int t = 0; t < STAGES - 1; ++t)
+        if (t < n_tiles) issue_tile_loads(t);
+    wait_vm<0>();
+    __syncthreads();
+
+    // ---- main loops over blocks of 32 keys
+    const int n_kblocks = 2 * n_tiles;
+    int b = 0;
+    floatx16 x[QB];
+    float mx[QB];
+    auto block_begin = [&](int blk) {  // at the first block of a tile: start streaming tile j + STAGES - 1
+        if ((blk & 1) == 0) {
+            const int t = (blk >> 1) + STAGES - 1;
+            if (t < n_tiles) issue_tile_loads(t);  // its stage was last read before the previous barrier
+        }
+    };
+    auto block_end = [&](int blk) {  // after the last block of a tile: make tile j + 1 visible
+        if (blk & 1) {
+            if ((blk >> 1) + STAGES - 1 < n_tiles)
+                wait_vm<(STAGES - 2) * LOADS_PER_TILE>();
+            else
+                wait_vm<0>();
+            __syncthreads();
+        }
+    };
+    auto block_geom = [&](int blk, const char*& Kb, const char*& Vb, int& kbase, bool& active, bool& masked) {
+        const int j = blk >> 1, kb = blk & 1;
+        const char* st = smem + (j % STAGES) * C::STAGE;
+        Kb = st + kb * 32 * C::ROWB;
+        Vb = st + C::KBYTES + kb * 32 * C::ROWB;
+        kbase = j * BC + 32 * kb;
+        active = !CAUSAL || kbase <= q0w + QW - 1;
+        masked = (kbase + 32 > N) || (CAUSAL && kbase + 31 > q0w);
+    };
+
+    // Per wavefront the blocks fall into three consecutive ranges: fully visible, partly masked
+    // (sequence tail or causal diagonal), and not visible at all (the wavefront then only keeps
+    // streaming and synchronising for the others).  One loop per range keeps each loop body
+    // straight-line.
+    const int n_vis_blocks = (N + 31) / 32;
+    const int n_unm = CAUSAL ? min(q0w / 32, N / 32) : N / 32;
+    const int n_act = CAUSAL ? min(n_vis_blocks, (q0w + QW) / 32) : n_vis_blocks;
+#pragma unroll 1
+    for (; b < n_unm; ++b) {
+        const char *Kb, *Vb;
+        int kbase;
+        bool active, masked;
+        block_begin(b);
+        block_geom(b, Kb, Vb, kbase, active, masked);
+        front(Kb, kbase, false, x, mx);
+        if (needs_rescale(mx)) rescale(x, mx);
+        back(Vb, x);
+        block_end(b);
+    }
+#pragma unroll 1
+    for (; b < n_act; ++b) {
+        const char *Kb, *Vb;
+        int kbase;
+        bool active, masked;
+        block_begin(b);
+        block_geom(b, Kb, Vb, kbase, active, masked);
+        front(Kb, kbase, true, x, mx);
+        if (needs_rescale(mx)) rescale(x, mx);
+        back(Vb, x);
+        block_end(b);
+    }
+#pragma unroll 1
+    for (; b < n_kblocks; ++b) {
+        block_begin(b);
+        block_end(b);
     }
 
     // ---- epilogue: O = O_acc / l, rounded to bf16; a lane holds 4 consecutive head-dim elements per register quad
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const float inv = 1.0f / halves_sum(lsum[qb]);
+        const float inv = 1.0f / halves_sum(lsum[qb][0] + lsum[qb][1]);
         const int row = q0w + 32 * qb + l32;
         if (row < N) {
 #pragma unroll
@@ -261,16 +374,15 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
     }
 }
 
-template <int D, int QB, bool CAUSAL>
+template <int D, int QB, int STAGES, bool CAUSAL>
 static hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* O, int BH, int N, float scale,
                              hipStream_t stream) {
     constexpr int BR = 128 * QB;
     const int n_qtiles = (N + BR - 1) / BR;
-    const long long n_blocks_ll = (long long)BH * n_qtiles;
-    const int n_blocks = (int)n_blocks_ll;
+    const int n_blocks = BH * n_qtiles;
     const int blocks_per_xcd = (n_blocks + 7) / 8;
-    auto kern = fwd_bf16_kernel<D, QB, CAUSAL>;
-    constexpr int lds = Bf16Cfg<D>::LDS_BYTES;
+    auto kern = fwd_bf16_kernel<D, QB, STAGES, CAUSAL>;
+    constexpr int lds = Bf16Cfg<D, STAGES>::LDS_BYTES;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(blocks_per_xcd * 8), dim3(256), lds, stream, (const bf16*)Q, (const bf16*)K,
@@ -280,12 +392,14 @@ static hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* 
 
 hipError_t launch_fwd_bf16(const void* Q, const void* K, const void* V, void* O, int BH, int N, int d, float scale,
                            int causal, hipStream_t stream) {
+    // LDS: d = 64 -> 16 KiB per stage, 4 stages, two workgroups per CU = 128 KiB;
+    //      d = 128 -> 32 KiB per stage, 2 stages, two workgroups per CU = 128 KiB (of 160 KiB)
     if (d == 64) {
-        return causal ? launch_cfg<64, 2, true>(Q, K, V, O, BH, N, scale, stream)
-                      : launch_cfg<64, 2, false>(Q, K, V, O, BH, N, scale, stream);
+        return causal ? launch_cfg<64, 2, 4, true>(Q, K, V, O, BH, N, scale, stream)
+                      : launch_cfg<64, 2, 4, false>(Q, K, V, O, BH, N, scale, stream);
     }
-    return causal ? launch_cfg<128, 1, true>(Q, K, V, O, BH, N, scale, stream)
-                  : launch_cfg<128, 1, false>(Q, K, V, O, BH, N, scale, stream);
+    return causal ? launch_cfg<128, 1, 2, true>(Q, K, V, O, BH, N, scale, stream)
+                  : launch_cfg<128, 1, 2, false>(Q, K, V, O, BH, N, scale, stream);
 }
 
 }  // namespace flat

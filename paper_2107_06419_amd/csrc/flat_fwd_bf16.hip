@@ -2,8 +2,8 @@
 //
 // Dataflow (paper sections 4-5: fused Logit-softmax-Attend with a shared outer loop over batch,
 // head and blocks of query rows, the two inner loops interleaved):
-//   one workgroup = one (batch, head, block of BR query rows); its 4 wavefronts own QW = BR/4 rows
-//   each.  The key/value sequence is streamed in tiles of 64 keys through a ring of LDS stages
+//   one workgroup = one (batch, head, block of BR query rows); its NW wavefronts own QW = BR/NW
+//   rows each.  The key/value sequence is streamed in tiles of 64 keys through a ring of LDS stages
 //   (the paper's double-buffered operand tiles, deepened to hide HBM/L2 latency).  Each tile is
 //   consumed as two blocks of 32 keys; per block a wavefront computes
 //       S^T = K_blk Q^T            (Logit, MFMA 32x32x16 bf16; the transposed product is chosen so
@@ -36,7 +36,7 @@ constexpr float kRescaleSlack = 8.0f;  // log2 units
 // chunk index within a row: chunk c of row r lives in slot c ^ swz(r).  The LDS serves 256 bytes
 // per clock: a ds_read_b128 touches 16 rows at one chunk index per clock, a ds_read_b64_tr_b16
 // touches 4 rows x 64 bytes; swz() is chosen so that both patterns hit every bank once.
-template <int D, int STAGES>
+template <int D, int STAGES, int NW>
 struct Bf16Cfg {
     static constexpr int BC = 64;                     // keys per tile
     static constexpr int ROWB = D * 2;                // bytes per row
@@ -45,7 +45,7 @@ struct Bf16Cfg {
     static constexpr int VBYTES = BC * ROWB;
     static constexpr int STAGE = KBYTES + VBYTES;
     static constexpr int ROWS_PER_LOAD = 1024 / ROWB; // rows covered by one wave-wide 16-byte-per-lane load
-    static constexpr int LOADS = BC / ROWS_PER_LOAD / 4;  // such loads per wavefront per tensor per tile
+    static constexpr int LOADS = BC / ROWS_PER_LOAD / NW; // such loads per wavefront per tensor per tile
     static constexpr int LDS_BYTES = STAGES * STAGE;
     __device__ static __forceinline__ int swz(int r) {
         if (D == 64) return (((r >> 1) & 1) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1);  // 128-byte rows: 2 rows per 256 B
@@ -69,12 +69,12 @@ __device__ __forceinline__ void wait_vm() {
     __builtin_amdgcn_s_waitcnt((CNT & 15) | ((CNT >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-template <int D, int QB, int STAGES, bool CAUSAL>
-__global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
+template <int D, int QB, int NW, int STAGES, bool CAUSAL>
+__global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                           const bf16* __restrict__ V, bf16* __restrict__ O, int N,
                                                           int n_qtiles, int n_blocks, int blocks_per_xcd, float c) {
-    using C = Bf16Cfg<D, STAGES>;
-    constexpr int QW = 32 * QB, BR = 4 * QW, BC = C::BC, DS = D / 16, DB = D / 32;
+    using C = Bf16Cfg<D, STAGES, NW>;
+    constexpr int QW = 32 * QB, BR = NW * QW, BC = C::BC, DS = D / 16, DB = D / 32;
     constexpr int LOADS_PER_TILE = 2 * C::LOADS;  // DMA instructions per wavefront per tile (K and V)
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -143,23 +143,23 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
     const int n_tiles = (kv_len + BC - 1) / BC;
 
     // ---- global -> LDS streaming.  Wave w issues load i of a tile for the 1024-byte LDS block
-    // (4 i + w); lane l fills slot (l % CHUNKS) of row (l / CHUNKS) of that block, so it fetches
+    // (NW i + w); lane l fills slot (l % CHUNKS) of row (l / CHUNKS) of that block, so it fetches
     // the chunk whose swizzled position that is.  Keys beyond N are clamped to the last key: their
     // logits are masked and their (finite) values meet a zero probability.
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
     int ld_row[C::LOADS], ld_chunk_off[C::LOADS];
 #pragma unroll
     for (int i = 0; i < C::LOADS; ++i) {
-        ld_row[i] = (4 * i + wave) * C::ROWS_PER_LOAD + lane / C::CHUNKS;
+        ld_row[i] = (NW * i + wave) * C::ROWS_PER_LOAD + lane / C::CHUNKS;
         ld_chunk_off[i] = ((lane % C::CHUNKS) ^ C::swz(ld_row[i])) * 16;
     }
-    auto issue_tile_loads = [&](int tile) {
+    auto issue_tile_loads = [&](int tile) __attribute__((always_inline)) {
         const uint32_t stage_base = smem_base + (uint32_t)(tile % STAGES) * C::STAGE;
 #pragma unroll
         for (int i = 0; i < C::LOADS; ++i) {
             const int key = min(tile * BC + ld_row[i], N - 1);
             const uint32_t voff = (uint32_t)key * C::ROWB + ld_chunk_off[i];
-            const uint32_t lds_k = __builtin_amdgcn_readfirstlane(stage_base + (4 * i + wave) * 1024);
+            const uint32_t lds_k = __builtin_amdgcn_readfirstlane(stage_base + (NW * i + wave) * 1024);
             dma16(Kh, voff, lds_k);
             dma16(Vh, voff, lds_k + C::KBYTES);
         }
@@ -182,18 +182,47 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
         }
     const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
 
-    // ---- block = 32 keys.  front(): x = c S - m and the per-row maximum of x; back(): exponentials and Attend.
-    auto front = [&](const char* Kb, int kbase, bool masked, floatx16 (&x)[QB], float (&mx)[QB]) {
+    // ---- block = 32 keys.  Pieces of the per-block work; the main loop below software-pipelines them so
+    // that the matrix pipe works on PV of block b-1 and on S of block b+1 while the vector ALU does the
+    // softmax of block b.
+    auto read_k = [&](int blk, bf16x8 (&kf)[DS]) __attribute__((always_inline)) {  // K fragments (A operand of S^T = K Q^T) of one block
+        const char* Kb = smem + ((blk >> 1) % STAGES) * C::STAGE + (blk & 1) * 32 * C::ROWB;
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) kf[ds] = *(const bf16x8*)(Kb + koff[ds]);
+    };
+    auto read_v = [&](int blk, bf16x8 (&vf)[2][DB]) __attribute__((always_inline)) {  // V^T fragments (A operand of O^T += V^T P^T)
+        const char* Vb = smem + ((blk >> 1) % STAGES) * C::STAGE + C::KBYTES + (blk & 1) * 32 * C::ROWB;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const char* vrow = Vb + t * 16 * C::ROWB;  // swz() only looks at row bits below 16
+                vf[t][db] = concat(lds_read_tr16(vrow + voff[db][0]), lds_read_tr16(vrow + voff[db][1]));
+            }
+    };
+    auto logits = [&](const bf16x8 (&kf)[DS], floatx16 (&x)[QB]) __attribute__((always_inline)) {  // S^T = K Q^T
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) x[qb][r] = 0.f;
 #pragma unroll
-        for (int ds = 0; ds < DS; ++ds) {
-            const bf16x8 kf = *(const bf16x8*)(Kb + koff[ds]);
+        for (int ds = 0; ds < DS; ++ds)
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) x[qb] = mfma_bf16_32x32x16(kf, qf[qb][ds], x[qb]);
-        }
+            for (int qb = 0; qb < QB; ++qb) x[qb] = mfma_bf16_32x32x16(kf[ds], qf[qb][ds], x[qb]);
+    };
+    auto attend = [&](const bf16x8 (&vf)[2][DB], const uint32_t (&p)[QB][8]) __attribute__((always_inline)) {  // O^T += V^T P^T
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    uint4v pw = {p[qb][4 * t], p[qb][4 * t + 1], p[qb][4 * t + 2], p[qb][4 * t + 3]};
+                    oacc[qb][db] = mfma_bf16_32x32x16(vf[t][db], __builtin_bit_cast(bf16x8, pw), oacc[qb][db]);
+                }
+    };
+    // x <- c S - m (masked keys -> -inf), and the per-row maximum of x
+    auto softmax_a = [&](int blk, bool masked, floatx16 (&x)[QB], float (&mx)[QB]) __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             const float mref = m[qb];
@@ -203,7 +232,7 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
                 const int qidx = q0w + 32 * qb + l32;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int key = kbase + acc_row(r, half);
+                    const int key = blk * 32 + acc_row(r, half);
                     const bool ok = key < N && (!CAUSAL || key <= qidx);
                     x[qb][r] = ok ? x[qb][r] : -INFINITY;  // exp2 -> probability exactly 0
                 }
@@ -217,8 +246,8 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
             mx[qb] = halves_max(__builtin_fmaxf(a, b2));
         }
     };
-    auto back = [&](const char* Vb, floatx16 (&x)[QB]) {
-        uint32_t p[QB][8];
+    // p <- bf16(exp2(x)), l += sum of the ROUNDED probabilities (so that sum and Attend operand agree)
+    auto softmax_b = [&](floatx16 (&x)[QB], uint32_t (&p)[QB][8]) __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             float l0 = lsum[qb][0], l1 = lsum[qb][1];
@@ -230,33 +259,16 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
                 const uint32_t pk0 = pack_bf16(e[0], e[1]), pk1 = pack_bf16(e[2], e[3]);
                 p[qb][r >> 1] = pk0;
                 p[qb][(r >> 1) + 1] = pk1;
-                // row sum of the ROUNDED probabilities, so that the sum and the Attend operand agree
                 l0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0), ones, l0, false);
                 l1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1), ones, l1, false);
             }
             lsum[qb][0] = l0;
             lsum[qb][1] = l1;
         }
-        // Attend: O^T[dcol, query] += V^T[dcol, key] P^T[key, query]
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const char* vrow = Vb + t * 16 * C::ROWB;  // swz() only looks at row bits below 16
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const bf16x4 lo = lds_read_tr16(vrow + voff[db][0]);
-                const bf16x4 hi = lds_read_tr16(vrow + voff[db][1]);
-                const bf16x8 vf = concat(lo, hi);
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    uint4v pw = {p[qb][4 * t], p[qb][4 * t + 1], p[qb][4 * t + 2], p[qb][4 * t + 3]};
-                    oacc[qb][db] = mfma_bf16_32x32x16(vf, __builtin_bit_cast(bf16x8, pw), oacc[qb][db]);
-                }
-            }
-        }
     };
     // Rare path: raise the reference max of every row whose block maximum lies above it, rescale O and l,
     // and shift the block's exponents accordingly.
-    auto rescale = [&](floatx16 (&x)[QB], const float (&mx)[QB]) {
+    auto rescale = [&](floatx16 (&x)[QB], const float (&mx)[QB]) __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             const float delta = __builtin_fmaxf(mx[qb], 0.f);
@@ -269,10 +281,10 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(oacc[qb][db][r]) : "v"(alpha));
+                for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha;
         }
     };
-    auto needs_rescale = [&](const float (&mx)[QB]) {
+    auto needs_rescale = [&](const float (&mx)[QB]) __attribute__((always_inline)) {
         bool need = false;
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) need |= mx[qb] > kRescaleSlack;
@@ -287,71 +299,69 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
     wait_vm<0>();
     __syncthreads();
 
-    // ---- main loops over blocks of 32 keys
-    const int n_kblocks = 2 * n_tiles;
-    int b = 0;
-    floatx16 x[QB];
+    // Pipeline state: xA/xB hold the logits of the current / next block, pA/pB and vfA/vfB the
+    // probabilities and V fragments of the block whose Attend is still owed.
+    floatx16 xA[QB], xB[QB];
+    uint32_t pA[QB][8], pB[QB][8];
+    bf16x8 vfA[2][DB], vfB[2][DB];
+    bf16x8 kf[DS];
     float mx[QB];
-    auto block_begin = [&](int blk) {  // at the first block of a tile: start streaming tile j + STAGES - 1
-        if ((blk & 1) == 0) {
-            const int t = (blk >> 1) + STAGES - 1;
-            if (t < n_tiles) issue_tile_loads(t);  // its stage was last read before the previous barrier
-        }
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pB[qb][i] = 0u;  // the Attend owed before block 0 adds nothing
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) vfB[t][db] = __builtin_bit_cast(bf16x8, (uint4v){0, 0, 0, 0});
+    read_k(0, kf);
+    logits(kf, xA);
+
+    // One step = one block b:   matrix pipe: Attend(b-1), then S(b+1);   vector ALU: softmax(b).
+    // Stage bookkeeping (tile j = blocks 2j, 2j+1; reads of step b touch K of block b+1 and V of block b):
+    //   after step 2j   : wait for tile j+1, barrier  (also: every wave is past step 2j-1, the last reader of tile j-1)
+    //   before step 2j+1: start streaming tile j+STAGES-1 into the stage that held tile j-1
+    auto step = [&](int blk, bool masked, floatx16 (&xc)[QB], floatx16 (&xn)[QB], const uint32_t (&pp)[QB][8],
+                    const bf16x8 (&vp)[2][DB], uint32_t (&pc)[QB][8], bf16x8 (&vc)[2][DB]) __attribute__((always_inline)) {
+        read_k(blk + 1, kf);
+        attend(vp, pp);
+        softmax_a(blk, masked, xc, mx);
+        if (needs_rescale(mx)) rescale(xc, mx);
+        read_v(blk, vc);
+        logits(kf, xn);
+        softmax_b(xc, pc);
     };
-    auto block_end = [&](int blk) {  // after the last block of a tile: make tile j + 1 visible
-        if (blk & 1) {
-            if ((blk >> 1) + STAGES - 1 < n_tiles)
-                wait_vm<(STAGES - 2) * LOADS_PER_TILE>();
-            else
-                wait_vm<0>();
-            __syncthreads();
-        }
-    };
-    auto block_geom = [&](int blk, const char*& Kb, const char*& Vb, int& kbase, bool& active, bool& masked) {
-        const int j = blk >> 1, kb = blk & 1;
-        const char* st = smem + (j % STAGES) * C::STAGE;
-        Kb = st + kb * 32 * C::ROWB;
-        Vb = st + C::KBYTES + kb * 32 * C::ROWB;
-        kbase = j * BC + 32 * kb;
-        active = !CAUSAL || kbase <= q0w + QW - 1;
-        masked = (kbase + 32 > N) || (CAUSAL && kbase + 31 > q0w);
+    auto tile_steps = [&](int j, bool masked) __attribute__((always_inline)) {
+        step(2 * j, masked, xA, xB, pB, vfB, pA, vfA);
+        if (j + STAGES - 2 < n_tiles)
+            wait_vm<(STAGES - 3) * LOADS_PER_TILE>();
+        else
+            wait_vm<0>();
+        __syncthreads();
+        if (j + STAGES - 1 < n_tiles) issue_tile_loads(j + STAGES - 1);
+        step(2 * j + 1, masked, xB, xA, pA, vfA, pB, vfB);
     };
 
-    // Per wavefront the blocks fall into three consecutive ranges: fully visible, partly masked
+    // Per wavefront the tiles fall into three consecutive ranges: fully visible, partly masked
     // (sequence tail or causal diagonal), and not visible at all (the wavefront then only keeps
-    // streaming and synchronising for the others).  One loop per range keeps each loop body
-    // straight-line.
+    // streaming and synchronising for the others).
     const int n_vis_blocks = (N + 31) / 32;
-    const int n_unm = CAUSAL ? min(q0w / 32, N / 32) : N / 32;
-    const int n_act = CAUSAL ? min(n_vis_blocks, (q0w + QW) / 32) : n_vis_blocks;
+    const int n_unm_tiles = (CAUSAL ? min(q0w / 32, N / 32) : N / 32) / 2;
+    const int n_act_tiles = ((CAUSAL ? min(n_vis_blocks, (q0w + QW) / 32) : n_vis_blocks) + 1) / 2;
+    int j = 0;
 #pragma unroll 1
-    for (; b < n_unm; ++b) {
-        const char *Kb, *Vb;
-        int kbase;
-        bool active, masked;
-        block_begin(b);
-        block_geom(b, Kb, Vb, kbase, active, masked);
-        front(Kb, kbase, false, x, mx);
-        if (needs_rescale(mx)) rescale(x, mx);
-        back(Vb, x);
-        block_end(b);
-    }
+    for (; j < n_unm_tiles; ++j) tile_steps(j, false);
 #pragma unroll 1
-    for (; b < n_act; ++b) {
-        const char *Kb, *Vb;
-        int kbase;
-        bool active, masked;
-        block_begin(b);
-        block_geom(b, Kb, Vb, kbase, active, masked);
-        front(Kb, kbase, true, x, mx);
-        if (needs_rescale(mx)) rescale(x, mx);
-        back(Vb, x);
-        block_end(b);
-    }
+    for (; j < n_act_tiles; ++j) tile_steps(j, true);
+    attend(vfB, pB);  // the Attend still owed for the last block
 #pragma unroll 1
-    for (; b < n_kblocks; ++b) {
-        block_begin(b);
-        block_end(b);
+    for (; j < n_tiles; ++j) {
+        if (j + STAGES - 2 < n_tiles)
+            wait_vm<(STAGES - 3) * LOADS_PER_TILE>();
+        else
+            wait_vm<0>();
+        __syncthreads();
+        if (j + STAGES - 1 < n_tiles) issue_tile_loads(j + STAGES - 1);
     }
 
     // ---- epilogue: O = O_acc / l, rounded to bf16; a lane holds 4 consecutive head-dim elements per register quad
@@ -374,32 +384,32 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(const bf16* __restrict
     }
 }
 
-template <int D, int QB, int STAGES, bool CAUSAL>
+template <int D, int QB, int NW, int STAGES, bool CAUSAL>
 static hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* O, int BH, int N, float scale,
                              hipStream_t stream) {
-    constexpr int BR = 128 * QB;
+    constexpr int BR = 32 * QB * NW;
     const int n_qtiles = (N + BR - 1) / BR;
     const int n_blocks = BH * n_qtiles;
     const int blocks_per_xcd = (n_blocks + 7) / 8;
-    auto kern = fwd_bf16_kernel<D, QB, STAGES, CAUSAL>;
-    constexpr int lds = Bf16Cfg<D, STAGES>::LDS_BYTES;
+    auto kern = fwd_bf16_kernel<D, QB, NW, STAGES, CAUSAL>;
+    constexpr int lds = Bf16Cfg<D, STAGES, NW>::LDS_BYTES;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(blocks_per_xcd * 8), dim3(256), lds, stream, (const bf16*)Q, (const bf16*)K,
+    hipLaunchKernelGGL(kern, dim3(blocks_per_xcd * 8), dim3(64 * NW), lds, stream, (const bf16*)Q, (const bf16*)K,
                        (const bf16*)V, (bf16*)O, N, n_qtiles, n_blocks, blocks_per_xcd, scale * kLog2e);
     return hipGetLastError();
 }
 
 hipError_t launch_fwd_bf16(const void* Q, const void* K, const void* V, void* O, int BH, int N, int d, float scale,
                            int causal, hipStream_t stream) {
-    // LDS: d = 64 -> 16 KiB per stage, 4 stages, two workgroups per CU = 128 KiB;
-    //      d = 128 -> 32 KiB per stage, 2 stages, two workgroups per CU = 128 KiB (of 160 KiB)
+    // d = 64 : 4 waves x 64 rows, 16 KiB per stage x 4 stages, two workgroups per CU (128 of 160 KiB LDS)
+    // d = 128: 8 waves x 32 rows, 32 KiB per stage x 3 stages, one workgroup per CU (96 KiB)
     if (d == 64) {
-        return causal ? launch_cfg<64, 2, 4, true>(Q, K, V, O, BH, N, scale, stream)
-                      : launch_cfg<64, 2, 4, false>(Q, K, V, O, BH, N, scale, stream);
+        return causal ? launch_cfg<64, 2, 4, 4, true>(Q, K, V, O, BH, N, scale, stream)
+                      : launch_cfg<64, 2, 4, 4, false>(Q, K, V, O, BH, N, scale, stream);
     }
-    return causal ? launch_cfg<128, 1, 2, true>(Q, K, V, O, BH, N, scale, stream)
-                  : launch_cfg<128, 1, 2, false>(Q, K, V, O, BH, N, scale, stream);
+    return causal ? launch_cfg<128, 1, 8, 3, true>(Q, K, V, O, BH, N, scale, stream)
+                  : launch_cfg<128, 1, 8, 3, false>(Q, K, V, O, BH, N, scale, stream);
 }
 
 }  // namespace flat

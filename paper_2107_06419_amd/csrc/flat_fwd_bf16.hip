@@ -17,18 +17,21 @@
 // Unlike the paper's row-granularity tile, which keeps a whole R x N logit slab on chip, the row
 // max and sum are carried as running values, so on-chip state is independent of N.
 //
-// Reference max.  softmax is invariant to the constant subtracted per row, so m need not be the
-// exact running maximum.  It starts as the (scaled) logit of key 0, which every query sees, so the
-// row sum is at least 1 and can never underflow; it is raised (and O, l rescaled) only when a
-// block's maximum exceeds it by more than kRescaleSlack, which keeps every exponent
-// <= 2^kRescaleSlack.  For typical data that happens in the first blocks only, so the steady-state
-// loop carries a compare but no rescale.
+// Reference max and optimistic exponentiation.  softmax is invariant to the constant subtracted per
+// row, so m need not be the exact running maximum.  It starts as the (scaled) logit of key 0, which
+// every query sees, so the row sum is at least 1 relative to it and can never underflow.  The steady
+// state exponentiates against the current m WITHOUT computing the block maximum; a logit far above m
+// shows up as a jump of the fp32 row sum (more than kSumJump per lane and block, i.e. some
+// probability above 2^10), and only then the block takes the exact path: row maximum, raise m,
+// rescale O and l, recompute the block's probabilities.  Probabilities therefore stay below 2^14
+// relative to m, far inside bf16/fp32 range, and for typical data the exact path runs in the first
+// blocks only.
 #include "flat_common.hpp"
 #include "flat_launch.hpp"
 
 namespace flat {
 
-constexpr float kRescaleSlack = 8.0f;  // log2 units
+constexpr float kSumJump = 16384.0f;  // per lane and 32-key block: 16 probabilities
 
 // LDS tile layout.  Rows are stored unpadded (ROWB = 2 D bytes) because tiles arrive by
 // global_load_lds_dwordx4, which writes the 64 lanes of a wavefront to 1024 contiguous LDS bytes
@@ -221,8 +224,8 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
                     oacc[qb][db] = mfma_bf16_32x32x16(vf[t][db], __builtin_bit_cast(bf16x8, pw), oacc[qb][db]);
                 }
     };
-    // x <- c S - m (masked keys -> -inf), and the per-row maximum of x
-    auto softmax_a = [&](int blk, bool masked, floatx16 (&x)[QB], float (&mx)[QB]) __attribute__((always_inline)) {
+    // x <- c S - m (masked keys -> -inf)
+    auto shift = [&](int blk, bool masked, floatx16 (&x)[QB]) __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             const float mref = m[qb];
@@ -237,13 +240,15 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
                     x[qb][r] = ok ? x[qb][r] : -INFINITY;  // exp2 -> probability exactly 0
                 }
             }
-            float a = __builtin_fmaxf(x[qb][0], x[qb][1]), b2 = __builtin_fmaxf(x[qb][8], x[qb][9]);
+        }
+    };
+    auto row_max = [&](const floatx16 (&x)[QB], float (&mx)[QB]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int r = 2; r < 8; r += 2) {
-                a = __builtin_fmaxf(a, __builtin_fmaxf(x[qb][r], x[qb][r + 1]));
-                b2 = __builtin_fmaxf(b2, __builtin_fmaxf(x[qb][r + 8], x[qb][r + 9]));
-            }
-            mx[qb] = halves_max(__builtin_fmaxf(a, b2));
+        for (int qb = 0; qb < QB; ++qb) {
+            float a = x[qb][0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) a = __builtin_fmaxf(a, x[qb][r]);
+            mx[qb] = halves_max(a);
         }
     };
     // p <- bf16(exp2(x)), l += sum of the ROUNDED probabilities (so that sum and Attend operand agree)
@@ -284,13 +289,6 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
                 for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha;
         }
     };
-    auto needs_rescale = [&](const float (&mx)[QB]) __attribute__((always_inline)) {
-        bool need = false;
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) need |= mx[qb] > kRescaleSlack;
-        return __builtin_amdgcn_ballot_w64(need) != 0;
-    };
-
     // ---- prologue: fill STAGES-1 stages.  The full wait also retires the Q loads above, so that no
     // wait on them is left inside the loops (it would drain the prefetch ring every iteration).
 #pragma unroll
@@ -317,19 +315,47 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
     read_k(0, kf);
     logits(kf, xA);
 
-    // One step = one block b:   matrix pipe: Attend(b-1), then S(b+1);   vector ALU: softmax(b).
+    // One step = one block b:   matrix pipe: Attend(b-1) and S(b+1);   vector ALU: softmax(b).
     // Stage bookkeeping (tile j = blocks 2j, 2j+1; reads of step b touch K of block b+1 and V of block b):
     //   after step 2j   : wait for tile j+1, barrier  (also: every wave is past step 2j-1, the last reader of tile j-1)
     //   before step 2j+1: start streaming tile j+STAGES-1 into the stage that held tile j-1
     auto step = [&](int blk, bool masked, floatx16 (&xc)[QB], floatx16 (&xn)[QB], const uint32_t (&pp)[QB][8],
                     const bf16x8 (&vp)[2][DB], uint32_t (&pc)[QB][8], bf16x8 (&vc)[2][DB]) __attribute__((always_inline)) {
         read_k(blk + 1, kf);
-        attend(vp, pp);
-        softmax_a(blk, masked, xc, mx);
-        if (needs_rescale(mx)) rescale(xc, mx);
         read_v(blk, vc);
+        __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads at the top: they have a whole step to land
+        float l_before[QB][2];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            l_before[qb][0] = lsum[qb][0];
+            l_before[qb][1] = lsum[qb][1];
+        }
+        attend(vp, pp);
         logits(kf, xn);
+        shift(blk, masked, xc);
         softmax_b(xc, pc);
+        // one scheduling region: spread the MFMAs evenly through the softmax instructions
+        constexpr int kMfmaPerStep = 2 * QB * DB + QB * DS, kValuPerMfma = (QB * 48) / kMfmaPerStep;
+#pragma unroll
+        for (int g = 0; g < kMfmaPerStep; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);             // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);  // its share of the vector work
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        bool jump = false;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+            jump |= !((lsum[qb][0] - l_before[qb][0]) + (lsum[qb][1] - l_before[qb][1]) <= kSumJump);
+        if (__builtin_amdgcn_ballot_w64(jump) != 0) {  // exact path: xc still holds c S - m of this block
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                lsum[qb][0] = l_before[qb][0];
+                lsum[qb][1] = l_before[qb][1];
+            }
+            row_max(xc, mx);
+            rescale(xc, mx);
+            softmax_b(xc, pc);
+        }
     };
     auto tile_steps = [&](int j, bool masked) __attribute__((always_inline)) {
         step(2 * j, masked, xA, xB, pB, vfB, pA, vfA);

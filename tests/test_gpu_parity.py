@@ -174,3 +174,20 @@ def test_status_codes_on_device_buffers():
     with pytest.raises(fa.FlatAttnError) as e:
         fa.flat_attn_fwd(t96, t96, t96, torch.zeros_like(t96), 1.0, 0)
     assert e.value.status == -3
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("mask", [0, 1])
+def test_reference_max_is_raised_when_logits_grow_along_the_sequence(d, mask):
+    """Keys whose logits keep growing with the key index, plus one late key far above everything before
+    it: the running reference max must be raised many times (and once by a huge step), with O and the
+    row sum rescaled each time."""
+    w = synth.custom("grow", 1, 2, 1200, d, "bf16", mask, seed=91 + d)
+    q, k, v = synth.make_qkv(w)
+    ramp = np.linspace(0.25, 6.0, w.N, dtype=np.float32)[None, None, :, None]
+    k = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(k * ramp)).reshape(k.shape)
+    q = np.abs(q)                      # keeps q.k correlated with |k|: logits grow along the sequence
+    k = np.abs(k)
+    k[:, :, 900, :] *= 8.0             # exactly representable; a jump of hundreds of log2 units at key 900
+    got = to_host_f64(run_entry("fused", w, q, k, v))
+    check_close(got, oracle_rows(w, q, k, v), "bf16", w.name)

@@ -297,11 +297,14 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
     wait_vm<0>();
     __syncthreads();
 
+    // With d = 128 two sets of V fragments do not fit the register file next to the accumulators: then one
+    // set is used, refilled in the middle of each step right after the MFMAs that consumed it were issued.
+    constexpr bool kTwoVSets = (D == 64);
     // Pipeline state: xA/xB hold the logits of the current / next block, pA/pB and vfA/vfB the
     // probabilities and V fragments of the block whose Attend is still owed.
     floatx16 xA[QB], xB[QB];
     uint32_t pA[QB][8], pB[QB][8];
-    bf16x8 vfA[2][DB], vfB[2][DB];
+    bf16x8 vfA[2][DB], vfB[2][DB];  // vfB stays unused with one set
     bf16x8 kf[DS];
     float mx[QB];
 #pragma unroll
@@ -311,7 +314,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int db = 0; db < DB; ++db) vfB[t][db] = __builtin_bit_cast(bf16x8, (uint4v){0, 0, 0, 0});
+        for (int db = 0; db < DB; ++db) vfA[t][db] = vfB[t][db] = __builtin_bit_cast(bf16x8, (uint4v){0, 0, 0, 0});
     read_k(0, kf);
     logits(kf, xA);
 
@@ -322,7 +325,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
     auto step = [&](int blk, bool masked, floatx16 (&xc)[QB], floatx16 (&xn)[QB], const uint32_t (&pp)[QB][8],
                     const bf16x8 (&vp)[2][DB], uint32_t (&pc)[QB][8], bf16x8 (&vc)[2][DB]) __attribute__((always_inline)) {
         read_k(blk + 1, kf);
-        read_v(blk, vc);
+        if (kTwoVSets) read_v(blk, vc);
         __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads at the top: they have a whole step to land
         float l_before[QB][2];
 #pragma unroll
@@ -330,16 +333,37 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
             l_before[qb][0] = lsum[qb][0];
             l_before[qb][1] = lsum[qb][1];
         }
-        attend(vp, pp);
-        logits(kf, xn);
-        shift(blk, masked, xc);
-        softmax_b(xc, pc);
-        // one scheduling region: spread the MFMAs evenly through the softmax instructions
         constexpr int kMfmaPerStep = 2 * QB * DB + QB * DS, kValuPerMfma = (QB * 48) / kMfmaPerStep;
+        if (kTwoVSets) {
+            // one scheduling region: spread the MFMAs evenly through the softmax instructions
+            attend(vp, pp);
+            logits(kf, xn);
+            shift(blk, masked, xc);
+            softmax_b(xc, pc);
 #pragma unroll
-        for (int g = 0; g < kMfmaPerStep; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);             // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);  // its share of the vector work
+            for (int g = 0; g < kMfmaPerStep; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);             // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);  // its share of the vector work
+            }
+        } else {
+            // two regions; the single V fragment set (vp and vc are the same registers) is refilled between them
+            attend(vp, pp);
+            shift(blk, masked, xc);
+#pragma unroll
+            for (int g = 0; g < 2 * QB * DB; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, (QB * 16) / (2 * QB * DB), 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            read_v(blk, vc);
+            __builtin_amdgcn_sched_barrier(0);
+            logits(kf, xn);
+            softmax_b(xc, pc);
+#pragma unroll
+            for (int g = 0; g < QB * DS; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, (QB * 32) / (QB * DS), 0);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
         bool jump = false;
@@ -358,14 +382,20 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
         }
     };
     auto tile_steps = [&](int j, bool masked) __attribute__((always_inline)) {
-        step(2 * j, masked, xA, xB, pB, vfB, pA, vfA);
+        if (kTwoVSets)
+            step(2 * j, masked, xA, xB, pB, vfB, pA, vfA);
+        else
+            step(2 * j, masked, xA, xB, pB, vfA, pA, vfA);
         if (j + STAGES - 2 < n_tiles)
             wait_vm<(STAGES - 3) * LOADS_PER_TILE>();
         else
             wait_vm<0>();
         __syncthreads();
         if (j + STAGES - 1 < n_tiles) issue_tile_loads(j + STAGES - 1);
-        step(2 * j + 1, masked, xB, xA, pA, vfA, pB, vfB);
+        if (kTwoVSets)
+            step(2 * j + 1, masked, xB, xA, pA, vfA, pB, vfB);
+        else
+            step(2 * j + 1, masked, xB, xA, pA, vfA, pB, vfA);
     };
 
     // Per wavefront the tiles fall into three consecutive ranges: fully visible, partly masked
@@ -379,7 +409,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
     for (; j < n_unm_tiles; ++j) tile_steps(j, false);
 #pragma unroll 1
     for (; j < n_act_tiles; ++j) tile_steps(j, true);
-    attend(vfB, pB);  // the Attend still owed for the last block
+    attend(kTwoVSets ? vfB : vfA, pB);  // the Attend still owed for the last block
 #pragma unroll 1
     for (; j < n_tiles; ++j) {
         if (j + STAGES - 2 < n_tiles)

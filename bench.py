@@ -39,6 +39,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2_long_16k")
     ap.add_argument("--unfused-steps", type=int, default=3, help="timed launches of the unfused baseline (0 = skip)")
+    ap.add_argument("--mfma-probe-launches", type=int, default=24, help="launches of the MFMA-only probe per operand kind (0 = skip)")
     ap.add_argument("--cpu-rows-per-head", type=int, default=16384, help="oracle sample size (0 = skip the cpu_baseline leg)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -116,6 +117,24 @@ def main() -> int:
                    "max_abs_diff_vs_fused": float((out_u.float() - out.float()).abs().max().item())}
         del ws, out_u
 
+    # what the matrix pipe sustains by itself on this GPU (clock under load depends on the operands' power draw)
+    probe = None
+    if args.mfma_probe_launches > 0:
+        sink = torch.empty(fa.flat_attn_mfma_probe_sink_bytes() // 4, dtype=torch.float32, device="cuda")
+        iters = 16000
+        probe = {}
+        for name, rnd in (("constant_operands_tflops", False), ("random_operands_tflops", True)):
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.mfma_probe_launches + 1)]
+            evs[0].record(stream)
+            for i in range(args.mfma_probe_launches):
+                fa.flat_attn_mfma_probe(sink, iters, rnd, stream)
+                evs[i + 1].record(stream)
+            torch.cuda.synchronize()
+            tail = max(1, args.mfma_probe_launches // 4)  # the last quarter: clocks have settled
+            ms = evs[-tail - 1].elapsed_time(evs[-1]) / tail
+            probe[name] = round(fa.flat_attn_mfma_probe_flops(iters) / (ms * 1e-3) / 1e12, 1)
+        probe["fused_vs_random_operand_mfma"] = round(kernel_tflops / probe["random_operands_tflops"], 4)
+
     cpu = None
     if args.cpu_rows_per_head > 0:
         import oracle
@@ -159,6 +178,7 @@ def main() -> int:
                       "fused_measured": None if traffic is None else traffic.get("fused_bytes_per_launch"),
                       "unfused_measured": None if traffic is None else traffic.get("unfused_bytes_per_launch")},
         "unfused": unfused,
+        "mfma_probe": probe,
         "cpu_baseline": cpu,
     }
     print(json.dumps(rec))

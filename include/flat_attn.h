@@ -19,7 +19,7 @@
  *     bf16 (flat_attn_fwd, flat_attn_unfused) or float (flat_attn_fwd_f32).  All four must
  *     be 16-byte aligned.  Q, K, V are only read.  O must not overlap Q, K or V.
  *   - Self-attention: queries and keys both number N.  Any N >= 1 is accepted.  d is 64 or 128.
- *   - scale multiplies the logits before softmax.
+ *   - scale multiplies the logits before softmax; it must be finite and >= 0.
  *   - mask_kind: FLAT_MASK_NONE, or FLAT_MASK_CAUSAL (key j contributes to query i iff j <= i;
  *     a masked key has probability exactly 0).
  *   - stream is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
@@ -86,6 +86,20 @@ size_t flat_attn_unfused_workspace_bytes(int B, int H, int N, int d, int dtype);
 int flat_attn_unfused(const void* Q, const void* K, const void* V, void* O,
                       int B, int H, int N, int d, float scale, int mask_kind,
                       void* workspace, size_t workspace_bytes, int dtype, void* stream);
+
+/*
+ * Measurement aid, not part of the attention path: a bf16 MFMA-only loop (the instruction both
+ * contractions of the fused kernel run on) that shows what the matrix pipe sustains by itself on this
+ * GPU.  The paper's utilisation metric (section 6, "Evaluation metrics": ideal runtime = total computes /
+ * peak FLOPs) needs a peak; this gives the measured one next to the published one.
+ *   sink: device, 16-byte aligned, at least flat_attn_mfma_probe_sink_bytes() bytes, overwritten.
+ *   iters: rounds of four independent 32x32x16 MFMAs per wavefront (rounded up to a multiple of 4).
+ *   random_operands: 0 = constant operands (1, 0); non-zero = pseudo-random operands in [-2, 2).
+ * One launch performs flat_attn_mfma_probe_flops(iters) floating-point operations; the caller times it.
+ */
+size_t flat_attn_mfma_probe_sink_bytes(void);
+double flat_attn_mfma_probe_flops(int iters);
+int flat_attn_mfma_probe(void* sink, size_t sink_bytes, int iters, int random_operands, void* stream);
 
 /* Human-readable name of a flat_status value (static storage, never NULL). */
 const char* flat_attn_status_string(int status);

@@ -46,6 +46,12 @@ def load_library():
     lib.flat_attn_unfused_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.flat_attn_unfused.restype = i
     lib.flat_attn_unfused.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, vp, sz, i, vp]
+    lib.flat_attn_mfma_probe_sink_bytes.restype = sz
+    lib.flat_attn_mfma_probe_sink_bytes.argtypes = []
+    lib.flat_attn_mfma_probe_flops.restype = ctypes.c_double
+    lib.flat_attn_mfma_probe_flops.argtypes = [i]
+    lib.flat_attn_mfma_probe.restype = i
+    lib.flat_attn_mfma_probe.argtypes = [vp, sz, i, i, vp]
     lib.flat_attn_status_string.restype = ctypes.c_char_p
     lib.flat_attn_status_string.argtypes = [i]
     lib.flat_attn_version.restype = i
@@ -118,3 +124,19 @@ def flat_attn_unfused(Q, K, V, O, scale: float, mask_kind: int, workspace, strea
     _check(load_library().flat_attn_unfused(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
                                             float(scale), int(mask_kind), workspace.data_ptr(), nbytes,
                                             FLAT_DTYPE_BF16, _stream_handle(stream)))
+
+
+def flat_attn_mfma_probe_sink_bytes() -> int:
+    return int(load_library().flat_attn_mfma_probe_sink_bytes())
+
+
+def flat_attn_mfma_probe_flops(iters: int) -> float:
+    return float(load_library().flat_attn_mfma_probe_flops(int(iters)))
+
+
+def flat_attn_mfma_probe(sink, iters: int, random_operands: bool, stream=None) -> None:
+    """MFMA-only throughput probe; `sink` is a device tensor of at least flat_attn_mfma_probe_sink_bytes() bytes."""
+    if not sink.is_cuda or not sink.is_contiguous():
+        raise ValueError("sink must be a contiguous GPU tensor")
+    _check(load_library().flat_attn_mfma_probe(sink.data_ptr(), sink.numel() * sink.element_size(), int(iters),
+                                               1 if random_operands else 0, _stream_handle(stream)))

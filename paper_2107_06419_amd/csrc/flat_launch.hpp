@@ -16,4 +16,10 @@ hipError_t launch_fwd_f32(const float* Q, const float* K, const float* V, float*
 hipError_t launch_unfused_bf16(const void* Q, const void* K, const void* V, void* O, int BH, int N, int d, float scale,
                                int causal, float* L, hipStream_t stream);
 
+// MFMA-only throughput probe (flat_probe.hip): 512 workgroups x 4 wavefronts, each issuing `iters` rounds of
+// four independent 32x32x16 bf16 MFMAs.  `sink` receives one float per thread.
+hipError_t launch_mfma_probe(float* sink, int iters, int random_operands, hipStream_t stream);
+double mfma_probe_flops(int iters);
+size_t mfma_probe_sink_bytes();
+
 }  // namespace flat

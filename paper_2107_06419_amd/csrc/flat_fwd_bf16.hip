@@ -156,8 +156,8 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
         ld_row[i] = (NW * i + wave) * C::ROWS_PER_LOAD + lane / C::CHUNKS;
         ld_chunk_off[i] = ((lane % C::CHUNKS) ^ C::swz(ld_row[i])) * 16;
     }
-    auto issue_tile_loads = [&](int tile) __attribute__((always_inline)) {
-        const uint32_t stage_base = smem_base + (uint32_t)(tile % STAGES) * C::STAGE;
+    auto issue_tile_loads = [&](int tile, int stage) __attribute__((always_inline)) {  // stage = tile % STAGES
+        const uint32_t stage_base = smem_base + (uint32_t)stage * C::STAGE;
 #pragma unroll
         for (int i = 0; i < C::LOADS; ++i) {
             const int key = min(tile * BC + ld_row[i], N - 1);
@@ -188,20 +188,29 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
     // ---- block = 32 keys.  Pieces of the per-block work; the main loop below software-pipelines them so
     // that the matrix pipe works on PV of block b-1 and on S of block b+1 while the vector ALU does the
     // softmax of block b.
-    auto read_k = [&](int blk, bf16x8 (&kf)[DS]) __attribute__((always_inline)) {  // K fragments (A operand of S^T = K Q^T) of one block
-        const char* Kb = smem + ((blk >> 1) % STAGES) * C::STAGE + (blk & 1) * 32 * C::ROWB;
+    // (stage, kb) locate a block: ring stage of its tile and which half of the tile.  In the unrolled main loop
+    // both are compile-time constants and fold into the immediate offsets of the LDS reads.
+    auto read_k = [&](int stage, int kb, bf16x8 (&kf)[DS]) __attribute__((always_inline)) {  // K fragments (A operand of S^T = K Q^T) of one block
+        const int block_off = stage * C::STAGE + kb * 32 * C::ROWB;
 #pragma unroll
-        for (int ds = 0; ds < DS; ++ds) kf[ds] = *(const bf16x8*)(Kb + koff[ds]);
+        for (int ds = 0; ds < DS; ++ds) {
+            int lane_off = koff[ds];
+            asm volatile("" : "+v"(lane_off));  // keeps lane_off + constant inside the loop, where it folds into the DS offset field
+            kf[ds] = *(const bf16x8*)(smem + lane_off + block_off);
+        }
     };
-    auto read_v = [&](int blk, bf16x8 (&vf)[2][DB]) __attribute__((always_inline)) {  // V^T fragments (A operand of O^T += V^T P^T)
-        const char* Vb = smem + ((blk >> 1) % STAGES) * C::STAGE + C::KBYTES + (blk & 1) * 32 * C::ROWB;
+    auto read_v = [&](int stage, int kb, bf16x8 (&vf)[2][DB]) __attribute__((always_inline)) {  // V^T fragments (A operand of O^T += V^T P^T)
+        const int block_off = stage * C::STAGE + C::KBYTES + kb * 32 * C::ROWB;
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int db = 0; db < DB; ++db) {
+            int lo = voff[db][0], hi = voff[db][1];
+            asm volatile("" : "+v"(lo), "+v"(hi));
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const char* vrow = Vb + t * 16 * C::ROWB;  // swz() only looks at row bits below 16
-                vf[t][db] = concat(lds_read_tr16(vrow + voff[db][0]), lds_read_tr16(vrow + voff[db][1]));
+            for (int t = 0; t < 2; ++t) {
+                const int off = block_off + t * 16 * C::ROWB;  // swz() only looks at row bits below 16
+                vf[t][db] = concat(lds_read_tr16(smem + lo + off), lds_read_tr16(smem + hi + off));
             }
+        }
     };
     auto logits = [&](const bf16x8 (&kf)[DS], floatx16 (&x)[QB]) __attribute__((always_inline)) {  // S^T = K Q^T
 #pragma unroll
@@ -293,7 +302,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
     // wait on them is left inside the loops (it would drain the prefetch ring every iteration).
 #pragma unroll
     for (int t = 0; t < STAGES - 1; ++t)
-        if (t < n_tiles) issue_tile_loads(t);
+        if (t < n_tiles) issue_tile_loads(t, t);
     wait_vm<0>();
     __syncthreads();
 
@@ -315,17 +324,17 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
     for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int db = 0; db < DB; ++db) vfA[t][db] = vfB[t][db] = __builtin_bit_cast(bf16x8, (uint4v){0, 0, 0, 0});
-    read_k(0, kf);
+    read_k(0, 0, kf);
     logits(kf, xA);
 
     // One step = one block b:   matrix pipe: Attend(b-1) and S(b+1);   vector ALU: softmax(b).
     // Stage bookkeeping (tile j = blocks 2j, 2j+1; reads of step b touch K of block b+1 and V of block b):
     //   after step 2j   : wait for tile j+1, barrier  (also: every wave is past step 2j-1, the last reader of tile j-1)
     //   before step 2j+1: start streaming tile j+STAGES-1 into the stage that held tile j-1
-    auto step = [&](int blk, bool masked, floatx16 (&xc)[QB], floatx16 (&xn)[QB], const uint32_t (&pp)[QB][8],
+    auto step = [&](int blk, int stage, int next_stage, bool masked, floatx16 (&xc)[QB], floatx16 (&xn)[QB], const uint32_t (&pp)[QB][8],
                     const bf16x8 (&vp)[2][DB], uint32_t (&pc)[QB][8], bf16x8 (&vc)[2][DB]) __attribute__((always_inline)) {
-        read_k(blk + 1, kf);
-        if (kTwoVSets) read_v(blk, vc);
+        read_k(next_stage, (blk + 1) & 1, kf);
+        if (kTwoVSets) read_v(stage, blk & 1, vc);
         __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads at the top: they have a whole step to land
         float l_before[QB][2];
 #pragma unroll
@@ -355,7 +364,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
                 __builtin_amdgcn_sched_group_barrier(0x002, (QB * 16) / (2 * QB * DB), 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-            read_v(blk, vc);
+            read_v(stage, blk & 1, vc);
             __builtin_amdgcn_sched_barrier(0);
             logits(kf, xn);
             softmax_b(xc, pc);
@@ -381,21 +390,23 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
             softmax_b(xc, pc);
         }
     };
-    auto tile_steps = [&](int j, bool masked) __attribute__((always_inline)) {
+    auto tile_steps = [&](int j, int sj, bool masked) __attribute__((always_inline)) {  // sj = j % STAGES
+        const int sn = sj + 1 == STAGES ? 0 : sj + 1;       // stage of tile j+1
+        const int sd = sj == 0 ? STAGES - 1 : sj - 1;       // stage of tile j-1 = target of tile j+STAGES-1
         if (kTwoVSets)
-            step(2 * j, masked, xA, xB, pB, vfB, pA, vfA);
+            step(2 * j, sj, sj, masked, xA, xB, pB, vfB, pA, vfA);
         else
-            step(2 * j, masked, xA, xB, pB, vfA, pA, vfA);
+            step(2 * j, sj, sj, masked, xA, xB, pB, vfA, pA, vfA);
         if (j + STAGES - 2 < n_tiles)
             wait_vm<(STAGES - 3) * LOADS_PER_TILE>();
         else
             wait_vm<0>();
         __syncthreads();
-        if (j + STAGES - 1 < n_tiles) issue_tile_loads(j + STAGES - 1);
+        if (j + STAGES - 1 < n_tiles) issue_tile_loads(j + STAGES - 1, sd);
         if (kTwoVSets)
-            step(2 * j + 1, masked, xB, xA, pA, vfA, pB, vfB);
+            step(2 * j + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfB);
         else
-            step(2 * j + 1, masked, xB, xA, pA, vfA, pB, vfA);
+            step(2 * j + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfA);
     };
 
     // Per wavefront the tiles fall into three consecutive ranges: fully visible, partly masked
@@ -405,10 +416,19 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
     const int n_unm_tiles = (CAUSAL ? min(q0w / 32, N / 32) : N / 32) / 2;
     const int n_act_tiles = ((CAUSAL ? min(n_vis_blocks, (q0w + QW) / 32) : n_vis_blocks) + 1) / 2;
     int j = 0;
+    // main loop: STAGES fully visible tiles per trip, so that every ring stage index is a constant
 #pragma unroll 1
-    for (; j < n_unm_tiles; ++j) tile_steps(j, false);
+    for (; j + STAGES <= n_unm_tiles; j += STAGES) {
+#pragma unroll
+        for (int sj = 0; sj < STAGES; ++sj) tile_steps(j + sj, sj, false);
+    }
+    // remaining visible tiles and the partly masked ones (masking a fully visible tile changes nothing)
+    int sj = 0;  // j is a multiple of STAGES here
 #pragma unroll 1
-    for (; j < n_act_tiles; ++j) tile_steps(j, true);
+    for (; j < n_act_tiles; ++j) {
+        tile_steps(j, sj, true);
+        sj = sj + 1 == STAGES ? 0 : sj + 1;
+    }
     attend(kTwoVSets ? vfB : vfA, pB);  // the Attend still owed for the last block
 #pragma unroll 1
     for (; j < n_tiles; ++j) {
@@ -417,7 +437,8 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
         else
             wait_vm<0>();
         __syncthreads();
-        if (j + STAGES - 1 < n_tiles) issue_tile_loads(j + STAGES - 1);
+        if (j + STAGES - 1 < n_tiles) issue_tile_loads(j + STAGES - 1, sj == 0 ? STAGES - 1 : sj - 1);
+        sj = sj + 1 == STAGES ? 0 : sj + 1;
     }
 
     // ---- epilogue: O = O_acc / l, rounded to bf16; a lane holds 4 consecutive head-dim elements per register quad

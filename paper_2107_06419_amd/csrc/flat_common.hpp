@@ -46,6 +46,13 @@ __device__ __forceinline__ bf16x4 lds_read_tr16(const void* lds_ptr) {
     return __builtin_bit_cast(bf16x4, t);
 }
 
+// Same, from a 32-bit LDS byte address.
+__device__ __forceinline__ bf16x4 lds_read_tr16_at(int lds_addr) {
+    typedef short4v __attribute__((address_space(3))) * lds_s4_ptr;
+    short4v t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(uintptr_t)(uint32_t)lds_addr);
+    return __builtin_bit_cast(bf16x4, t);
+}
+
 __device__ __forceinline__ bf16x8 concat(bf16x4 lo, bf16x4 hi) {
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }

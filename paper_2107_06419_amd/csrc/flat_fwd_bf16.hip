@@ -168,11 +168,11 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
         }
     };
 
-    // per-lane LDS byte offsets of the MFMA operand reads (row part + swizzled chunk), one per
+    // per-lane LDS byte addresses of the MFMA operand reads (ring base + row part + swizzled chunk), one per
     // compile-time chunk index
     int koff[DS];
 #pragma unroll
-    for (int ds = 0; ds < DS; ++ds) koff[ds] = l32 * C::ROWB + (((2 * ds + half) ^ C::swz(l32)) << 4);
+    for (int ds = 0; ds < DS; ++ds) koff[ds] = (int)smem_base + l32 * C::ROWB + (((2 * ds + half) ^ C::swz(l32)) << 4);
     const int i16 = lane & 15, g16 = lane >> 4;
     int voff[DB][2];
 #pragma unroll
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
         for (int hi = 0; hi < 2; ++hi) {
             const int r = 8 * hi + 4 * (g16 >> 1) + (i16 >> 2);         // row within a 16-key step
             const int ch = 4 * db + 2 * (g16 & 1) + ((i16 >> 1) & 1);  // 16-byte chunk holding this lane's 4 columns
-            voff[db][hi] = r * C::ROWB + ((ch ^ C::swz(r)) << 4) + (i16 & 1) * 8;
+            voff[db][hi] = (int)smem_base + r * C::ROWB + ((ch ^ C::swz(r)) << 4) + (i16 & 1) * 8;
         }
     const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
 
@@ -191,24 +191,25 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
     // (stage, kb) locate a block: ring stage of its tile and which half of the tile.  In the unrolled main loop
     // both are compile-time constants and fold into the immediate offsets of the LDS reads.
     auto read_k = [&](int stage, int kb, bf16x8 (&kf)[DS]) __attribute__((always_inline)) {  // K fragments (A operand of S^T = K Q^T) of one block
+        typedef const bf16x8 __attribute__((address_space(3))) * lds_frag_ptr;
         const int block_off = stage * C::STAGE + kb * 32 * C::ROWB;
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) {
-            int lane_off = koff[ds];
-            asm volatile("" : "+v"(lane_off));  // keeps lane_off + constant inside the loop, where it folds into the DS offset field
-            kf[ds] = *(const bf16x8*)(smem + lane_off + block_off);
+            // Declaring the lane offset "modified" keeps (offset + constant) from being hoisted out of the loop
+            // into one register per stage; inside the loop the constant folds into the DS offset field.
+            asm volatile("" : "+v"(koff[ds]));
+            kf[ds] = *(lds_frag_ptr)(uintptr_t)(uint32_t)(koff[ds] + block_off);
         }
     };
     auto read_v = [&](int stage, int kb, bf16x8 (&vf)[2][DB]) __attribute__((always_inline)) {  // V^T fragments (A operand of O^T += V^T P^T)
         const int block_off = stage * C::STAGE + C::KBYTES + kb * 32 * C::ROWB;
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-            int lo = voff[db][0], hi = voff[db][1];
-            asm volatile("" : "+v"(lo), "+v"(hi));
+            asm volatile("" : "+v"(voff[db][0]), "+v"(voff[db][1]));
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const int off = block_off + t * 16 * C::ROWB;  // swz() only looks at row bits below 16
-                vf[t][db] = concat(lds_read_tr16(smem + lo + off), lds_read_tr16(smem + hi + off));
+                vf[t][db] = concat(lds_read_tr16_at(voff[db][0] + off), lds_read_tr16_at(voff[db][1] + off));
             }
         }
     };
@@ -260,11 +261,12 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
             mx[qb] = halves_max(a);
         }
     };
-    // p <- bf16(exp2(x)), l += sum of the ROUNDED probabilities (so that sum and Attend operand agree)
-    auto softmax_b = [&](floatx16 (&x)[QB], uint32_t (&p)[QB][8]) __attribute__((always_inline)) {
+    // p <- bf16(exp2(x)); bsum <- this block's sum of the ROUNDED probabilities (so that the row sum and the
+    // Attend operand agree), two partial sums per query block
+    auto softmax_b = [&](floatx16 (&x)[QB], uint32_t (&p)[QB][8], float (&bsum)[QB][2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            float l0 = lsum[qb][0], l1 = lsum[qb][1];
+            float l0 = 0.f, l1 = 0.f;
 #pragma unroll
             for (int r = 0; r < 16; r += 4) {
                 float e[4];
@@ -276,8 +278,8 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
                 l0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0), ones, l0, false);
                 l1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1), ones, l1, false);
             }
-            lsum[qb][0] = l0;
-            lsum[qb][1] = l1;
+            bsum[qb][0] = l0;
+            bsum[qb][1] = l1;
         }
     };
     // Rare path: raise the reference max of every row whose block maximum lies above it, rescale O and l,
@@ -336,19 +338,14 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
         read_k(next_stage, (blk + 1) & 1, kf);
         if (kTwoVSets) read_v(stage, blk & 1, vc);
         __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads at the top: they have a whole step to land
-        float l_before[QB][2];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            l_before[qb][0] = lsum[qb][0];
-            l_before[qb][1] = lsum[qb][1];
-        }
+        float bsum[QB][2];
         constexpr int kMfmaPerStep = 2 * QB * DB + QB * DS, kValuPerMfma = (QB * 48) / kMfmaPerStep;
         if (kTwoVSets) {
             // one scheduling region: spread the MFMAs evenly through the softmax instructions
             attend(vp, pp);
             logits(kf, xn);
             shift(blk, masked, xc);
-            softmax_b(xc, pc);
+            softmax_b(xc, pc, bsum);
 #pragma unroll
             for (int g = 0; g < kMfmaPerStep; ++g) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);             // one MFMA
@@ -367,7 +364,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
             read_v(stage, blk & 1, vc);
             __builtin_amdgcn_sched_barrier(0);
             logits(kf, xn);
-            softmax_b(xc, pc);
+            softmax_b(xc, pc, bsum);
 #pragma unroll
             for (int g = 0; g < QB * DS; ++g) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -377,17 +374,16 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_bf16_kernel(const bf16* __rest
         __builtin_amdgcn_sched_barrier(0);
         bool jump = false;
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-            jump |= !((lsum[qb][0] - l_before[qb][0]) + (lsum[qb][1] - l_before[qb][1]) <= kSumJump);
+        for (int qb = 0; qb < QB; ++qb) jump |= !(bsum[qb][0] + bsum[qb][1] <= kSumJump);
         if (__builtin_amdgcn_ballot_w64(jump) != 0) {  // exact path: xc still holds c S - m of this block
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                lsum[qb][0] = l_before[qb][0];
-                lsum[qb][1] = l_before[qb][1];
-            }
             row_max(xc, mx);
             rescale(xc, mx);
-            softmax_b(xc, pc);
+            softmax_b(xc, pc, bsum);
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            lsum[qb][0] += bsum[qb][0];
+            lsum[qb][1] += bsum[qb][1];
         }
     };
     auto tile_steps = [&](int j, int sj, bool masked) __attribute__((always_inline)) {  // sj = j % STAGES

@@ -58,8 +58,11 @@ __global__ __launch_bounds__(256) void logits_kernel(const bf16* __restrict__ Q,
 }
 
 // ---------------------------------------------------------------------------------------------
-// 2. One workgroup per row: running (max, sum) pass, then a second pass that overwrites the row
-//    with exp(x - max) / sum.  Keys beyond the causal limit are written as exact zeros.
+// 2. One workgroup per row; the row is replaced by exp(x - max) / sum.  Keys beyond the causal limit are
+//    written as exact zeros.  Two forms:
+//    - softmax_row_regs: rows of up to 256 * 4 * CH logits (N a multiple of 4) are held in registers, CH
+//      float4 per thread, so memory sees one read and one write of the row;
+//    - softmax_row_stream: any N; a running (max, sum) pass and a second pass that reads the row again.
 __device__ __forceinline__ void online_combine(float& m, float& s, float m2, float s2) {
     const float mn = __builtin_fmaxf(m, m2);
     const float a = (m == -INFINITY) ? 0.f : __expf(m - mn);
@@ -68,8 +71,61 @@ __device__ __forceinline__ void online_combine(float& m, float& s, float m2, flo
     m = mn;
 }
 
+template <bool IS_MAX>
+__device__ __forceinline__ float block_reduce(float v, float* slots) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float o = __shfl_xor(v, off);
+        v = IS_MAX ? __builtin_fmaxf(v, o) : v + o;
+    }
+    if ((threadIdx.x & 63) == 0) slots[threadIdx.x >> 6] = v;
+    __syncthreads();
+    const float r0 = slots[0], r1 = slots[1], r2 = slots[2], r3 = slots[3];
+    return IS_MAX ? __builtin_fmaxf(__builtin_fmaxf(r0, r1), __builtin_fmaxf(r2, r3)) : (r0 + r1) + (r2 + r3);
+}
+
+template <bool CAUSAL, int CH>
+__global__ __launch_bounds__(256) void softmax_row_regs(float* __restrict__ L, int N) {
+    __shared__ float smax[4], ssum[4];
+    const size_t rowid = blockIdx.x;  // bh * N + i
+    const int i = (int)(rowid % (size_t)N);
+    float* row = L + rowid * (size_t)N;
+    const int nk = CAUSAL ? i + 1 : N;
+    const int tid = threadIdx.x;
+
+    floatx4 x[CH];
+    float m = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int j = (c * 256 + tid) * 4;
+        x[c] = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        if (j < nk) x[c] = *(const floatx4*)(row + j);  // j < nk <= N and N % 4 == 0, so j + 3 < N
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (CAUSAL && j + e >= nk) x[c][e] = -INFINITY;
+            m = __builtin_fmaxf(m, x[c][e]);
+        }
+    }
+    m = block_reduce<true>(m, smax);  // key 0 is always valid, so m is finite
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[c][e] = __expf(x[c][e] - m);  // masked and out-of-row slots: exp(-inf) = 0
+            s += x[c][e];
+        }
+    s = block_reduce<false>(s, ssum);
+    const float inv = 1.0f / s;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int j = (c * 256 + tid) * 4;
+        if (j < N) *(floatx4*)(row + j) = floatx4{x[c][0] * inv, x[c][1] * inv, x[c][2] * inv, x[c][3] * inv};
+    }
+}
+
 template <bool CAUSAL>
-__global__ __launch_bounds__(256) void softmax_kernel(float* __restrict__ L, int N) {
+__global__ __launch_bounds__(256) void softmax_row_stream(float* __restrict__ L, int N) {
     const size_t rowid = blockIdx.x;  // bh * N + i
     const int i = (int)(rowid % (size_t)N);
     float* row = L + rowid * (size_t)N;
@@ -102,7 +158,20 @@ __global__ __launch_bounds__(256) void softmax_kernel(float* __restrict__ L, int
 #pragma unroll
     for (int w = 1; w < 4; ++w) online_combine(m, s, sm[w], ss[w]);
     const float inv = 1.0f / s;
-    for (int j = tid; j < N; j += 256) row[j] = j < nk ? __expf(row[j] - m) * inv : 0.f;
+    for (int j = tid; j < N; j += 256) row[j] = (j < nk) ? __expf(row[j] - m) * inv : 0.f;
+}
+
+template <bool CAUSAL>
+static void launch_softmax(float* L, int BH, int N, hipStream_t stream) {
+    const dim3 grid((unsigned)((size_t)BH * N)), block(256);
+    if ((N & 3) == 0 && N <= 1024)
+        hipLaunchKernelGGL((softmax_row_regs<CAUSAL, 1>), grid, block, 0, stream, L, N);
+    else if ((N & 3) == 0 && N <= 4096)
+        hipLaunchKernelGGL((softmax_row_regs<CAUSAL, 4>), grid, block, 0, stream, L, N);
+    else if ((N & 3) == 0 && N <= 16384)
+        hipLaunchKernelGGL((softmax_row_regs<CAUSAL, 16>), grid, block, 0, stream, L, N);
+    else
+        hipLaunchKernelGGL((softmax_row_stream<CAUSAL>), grid, block, 0, stream, L, N);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -191,7 +260,7 @@ static hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* 
                        N, scale);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((softmax_kernel<CAUSAL>), dim3((unsigned)((size_t)BH * N)), dim3(256), 0, stream, L, N);
+    launch_softmax<CAUSAL>(L, BH, N, stream);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((attend_kernel<D, CAUSAL>), dim3(nt, BH), dim3(256), 0, stream, (const float*)L, (const bf16*)V,

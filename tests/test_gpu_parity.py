@@ -4,6 +4,7 @@ sampled rows (each oracle row is independent) and through properties that need n
 import numpy as np
 import pytest
 
+import oracle
 from paper_2107_06419_amd import synth
 from helpers import check_close, errors, oracle_rows, sample_rows, to_device, to_host_f64
 
@@ -150,6 +151,34 @@ def test_unfused_matches_fused_mid_size():
         check_close(to_host_f64(a[:, :, idx, :]), ref, "bf16", "fused mid")
         check_close(to_host_f64(b[:, :, idx, :]), ref, "bf16", "unfused mid")
         print("fused vs unfused", errors(to_host_f64(a), to_host_f64(b)), flush=True)
+
+
+@pytest.mark.parametrize("N", [1000, 1023, 1028, 4096, 4100, 16384, 16388])
+@pytest.mark.parametrize("mask", [0, 1])
+def test_unfused_workspace_holds_the_probabilities(N, mask):
+    """On return the workspace is A = softmax_row(L) in fp32 (masked keys exactly 0).  The row lengths
+    cover every form of the row-softmax kernel: rows held on chip with 1, 4 and 16 vectors per thread,
+    and the streaming form (N not a multiple of 4, or beyond the on-chip limit)."""
+    import torch
+    import paper_2107_06419_amd as fa
+    w = synth.custom("probs", 1, 1, N, 64, "bf16", mask, seed=77 + N + mask)
+    q, k, v = synth.make_qkv(w)
+    dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+    out = torch.empty_like(dq)
+    ws = torch.full((N * N,), float("nan"), dtype=torch.float32, device="cuda")
+    print(f"case unfused probabilities {w}", flush=True)
+    fa.flat_attn_unfused(dq, dk, dv, out, w.scale, w.mask, ws)
+    torch.cuda.synchronize()
+    rows = sample_rows(N, 6, seed=N)
+    got = ws.view(N, N)[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+    _, A = oracle.logits_softmax(q[0, 0], k[0, 0], w.scale, w.mask, rows=rows)
+    assert np.isfinite(got).all()
+    assert np.abs(got - A).max() <= 2e-6, np.abs(got - A).max()      # fp32 exp and sum of <= 16K terms
+    assert np.abs(got.sum(axis=1) - 1.0).max() <= 1e-5
+    if mask:
+        for r, i in enumerate(rows):
+            assert (got[r, i + 1:] == 0.0).all()
+    check_close(to_host_f64(out[:, :, torch.from_numpy(rows).cuda(), :]), oracle_rows(w, q, k, v, rows=rows), "bf16", w.name)
 
 
 def test_status_codes_on_device_buffers():

@@ -61,6 +61,7 @@ typedef enum { FLAT_DTYPE_BF16 = 0 } flat_dtype;
  * Logit-softmax-Attend at row granularity).  Probabilities are rounded to bf16 before the
  * second contraction; row maxima and row sums are kept in fp32.
  *   Q, K, V: device, const bf16 [B,H,N,d].   O: device, bf16 [B,H,N,d], fully overwritten.
+ *   One head of one tensor (N*d*2 bytes) must stay below 4 GiB, else FLAT_ERR_SHAPE.
  */
 int flat_attn_fwd(const void* Q, const void* K, const void* V, void* O,
                   int B, int H, int N, int d, float scale, int mask_kind, void* stream);

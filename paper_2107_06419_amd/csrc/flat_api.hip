@@ -46,6 +46,7 @@ int flat_attn_fwd(const void* Q, const void* K, const void* V, void* O, int B, i
                   int mask_kind, void* stream) {
     const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 2);
     if (rc != FLAT_OK) return rc;
+    if ((unsigned long long)N * (unsigned)d * 2u > 0xffffffffULL) return FLAT_ERR_SHAPE;  // the kernel addresses one head with 32-bit byte offsets
     const hipError_t e = flat::launch_fwd_bf16(Q, K, V, O, B * H, N, d, scale, mask_kind == FLAT_MASK_CAUSAL,
                                                static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;

@@ -11,6 +11,7 @@ import sys
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="cfg2_long_16k")
+    ap.add_argument("--shape", default="", help="B,H,N,d,mask of a bf16 problem to run instead of a named workload")
     ap.add_argument("--reps", type=int, default=3)
     ap.add_argument("--unfused", action="store_true")
     ap.add_argument("--copy-mib", type=int, default=1024, help="size of the calibration copy (MiB read + MiB written)")
@@ -22,7 +23,11 @@ def main() -> int:
     import paper_2107_06419_amd as fa
     from paper_2107_06419_amd import synth
 
-    w = synth.WORKLOADS[args.workload]
+    if args.shape:
+        B, H, N, d, mask = (int(t) for t in args.shape.split(","))
+        w = synth.custom("shape_" + args.shape.replace(",", "_"), B, H, N, d, "bf16", mask, seed=1)
+    else:
+        w = synth.WORKLOADS[args.workload]
     q, k, v = synth.make_qkv(w)
 
     def dev(x):
@@ -47,7 +52,7 @@ def main() -> int:
         for _ in range(args.reps):
             dst.copy_(src)
         torch.cuda.synchronize()
-    print("profile_driver done", args.workload, flush=True)
+    print("profile_driver done", w.name, flush=True)
     return 0
 
 

@@ -59,6 +59,8 @@ def test_validation_happens_before_any_gpu_work():
     assert fwd(Q=ok[0] + 8) == -4 and fwd(O=ok[3] + 2) == -4
     assert fwd(O=ok[0]) == -7 and fwd(O=ok[1] + 16) == -7
     assert fwd(B=1 << 20, H=1 << 20, N=1 << 20) == -2           # index overflow
+    far = (0x1000, 1 << 40, 2 << 40, 3 << 40)
+    assert fwd(*far, N=1 << 24, d=128) == -2 and fwd(*far, N=1 << 25, d=64) == -2  # one head reaches 4 GiB
     assert lib.flat_attn_fwd_f32(ok[0], ok[1], ok[2], ok[3], 1, 1, 8, 48, 1.0, 0, None) == -3
 
     assert fa.flat_attn_unfused_workspace_bytes(1, 16, 16384, 64) == 16 * 16384 * 16384 * 4

@@ -89,6 +89,36 @@ int flat_attn_unfused(const void* Q, const void* K, const void* V, void* O,
                       void* workspace, size_t workspace_bytes, int dtype, void* stream);
 
 /*
+ * Tile shapes of the fused bf16 kernel.  The paper picks its tile sizes by a map-space exploration over a
+ * cost model (section 6.1) and discusses what the row granularity trades (section 5.3: fewer query rows per
+ * tile re-fetch the keys more often and fill the compute array less; more rows need more on-chip memory).
+ * Here the exploration is done by measurement: the library is built with several shapes per head dimension,
+ * flat_attn_fwd uses index 0, and flat_attn_fwd_tile runs any of them so that the choice can be re-timed.
+ *   flat_attn_tile_shape_count(d): number of shapes for head dimension d (0 if d is not 64 or 128).
+ *   flat_attn_tile_shape_get: fills *out (HOST pointer) for 0 <= index < count; FLAT_ERR_SHAPE otherwise.
+ *   flat_attn_tile_shape_occupancy: workgroups of that shape resident per compute unit on the current
+ *     device (registers and LDS permitting), or a negative flat_status; the only one of the three that
+ *     needs a GPU.
+ *   flat_attn_fwd_tile: flat_attn_fwd with the shape chosen by the caller; same arguments, checks and
+ *     result tolerance (different shapes sum in different orders, so results differ in the last bits).
+ */
+typedef struct {
+    int d;                  /* head dimension the shape is built for */
+    int rows_per_workgroup; /* query rows per workgroup (the paper's R of R-Gran) */
+    int keys_per_tile;      /* keys staged in LDS per ring stage */
+    int wavefronts;         /* wavefronts per workgroup */
+    int rows_per_wavefront; /* query rows owned by one wavefront */
+    int lds_stages;         /* depth of the K/V ring in LDS */
+    int lds_bytes;          /* LDS bytes per workgroup */
+} flat_tile_shape;
+
+int flat_attn_tile_shape_count(int d);
+int flat_attn_tile_shape_get(int d, int index, flat_tile_shape* out);
+int flat_attn_tile_shape_occupancy(int d, int index);
+int flat_attn_fwd_tile(const void* Q, const void* K, const void* V, void* O,
+                       int B, int H, int N, int d, float scale, int mask_kind, int tile_shape, void* stream);
+
+/*
  * Measurement aid, not part of the attention path: a bf16 MFMA-only loop (the instruction both
  * contractions of the fused kernel run on) that shows what the matrix pipe sustains by itself on this
  * GPU.  The paper's utilisation metric (section 6, "Evaluation metrics": ideal runtime = total computes /

@@ -24,6 +24,15 @@ class FlatAttnError(RuntimeError):
         self.status = status
 
 
+class FlatTileShape(ctypes.Structure):
+    """flat_tile_shape of the header, field for field."""
+    _fields_ = [(n, ctypes.c_int) for n in ("d", "rows_per_workgroup", "keys_per_tile", "wavefronts", "rows_per_wavefront",
+                                            "lds_stages", "lds_bytes")]
+
+    def as_dict(self) -> dict:
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -36,6 +45,12 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         raise FileNotFoundError(
             f"{_LIB_PATH} is missing: build it with `python -m paper_2107_06419_amd.build` (needs hipcc)")
+    # The device pointers and streams this binding hands over come from torch's HIP runtime.  Importing torch
+    # first makes the dynamic linker bind the library to that same runtime instead of loading a second one.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(_LIB_PATH)
     vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
     lib.flat_attn_fwd.restype = i
@@ -46,6 +61,14 @@ def load_library():
     lib.flat_attn_unfused_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.flat_attn_unfused.restype = i
     lib.flat_attn_unfused.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, vp, sz, i, vp]
+    lib.flat_attn_tile_shape_count.restype = i
+    lib.flat_attn_tile_shape_count.argtypes = [i]
+    lib.flat_attn_tile_shape_get.restype = i
+    lib.flat_attn_tile_shape_get.argtypes = [i, i, ctypes.POINTER(FlatTileShape)]
+    lib.flat_attn_tile_shape_occupancy.restype = i
+    lib.flat_attn_tile_shape_occupancy.argtypes = [i, i]
+    lib.flat_attn_fwd_tile.restype = i
+    lib.flat_attn_fwd_tile.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, i, vp]
     lib.flat_attn_mfma_probe_sink_bytes.restype = sz
     lib.flat_attn_mfma_probe_sink_bytes.argtypes = []
     lib.flat_attn_mfma_probe_flops.restype = ctypes.c_double
@@ -124,6 +147,32 @@ def flat_attn_unfused(Q, K, V, O, scale: float, mask_kind: int, workspace, strea
     _check(load_library().flat_attn_unfused(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
                                             float(scale), int(mask_kind), workspace.data_ptr(), nbytes,
                                             FLAT_DTYPE_BF16, _stream_handle(stream)))
+
+
+def flat_attn_tile_shape_count(d: int) -> int:
+    return int(load_library().flat_attn_tile_shape_count(int(d)))
+
+
+def flat_attn_tile_shape_get(d: int, index: int) -> FlatTileShape:
+    out = FlatTileShape()
+    _check(load_library().flat_attn_tile_shape_get(int(d), int(index), ctypes.byref(out)))
+    return out
+
+
+def flat_attn_tile_shape_occupancy(d: int, index: int) -> int:
+    """Workgroups of the shape resident per compute unit on the current device (needs a GPU)."""
+    n = int(load_library().flat_attn_tile_shape_occupancy(int(d), int(index)))
+    if n < 0:
+        _check(n)
+    return n
+
+
+def flat_attn_fwd_tile(Q, K, V, O, scale: float, mask_kind: int, tile_shape: int, stream=None) -> None:
+    """flat_attn_fwd with tile shape `tile_shape` of the library's table instead of the default (index 0)."""
+    import torch
+    B, H, N, d = _dev_args(torch.bfloat16, Q, K, V, O)
+    _check(load_library().flat_attn_fwd_tile(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
+                                             float(scale), int(mask_kind), int(tile_shape), _stream_handle(stream)))
 
 
 def flat_attn_mfma_probe_sink_bytes() -> int:

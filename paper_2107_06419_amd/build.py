@@ -10,7 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflat_attn.so")
-SOURCES = ["flat_api.hip", "flat_fwd_bf16.hip", "flat_fwd_f32.hip", "flat_unfused.hip", "flat_probe.hip"]
+SOURCES = ["flat_api.hip", "flat_fwd_bf16.hip", "flat_fwd_bf16_shapes_d64a.hip", "flat_fwd_bf16_shapes_d64b.hip",
+           "flat_fwd_bf16_shapes_d128.hip", "flat_tiles.hip", "flat_fwd_f32.hip", "flat_unfused.hip", "flat_probe.hip"]
 # packed fp32 VALU instructions are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
@@ -38,7 +39,7 @@ def _compile(src: str) -> str:
 def build_library(verbose: bool = True) -> str:
     """Compile every kernel source for gfx950 and link the shared library. Always recompiles."""
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=5) as pool:
+    with ThreadPoolExecutor(max_workers=8) as pool:
         objs = list(pool.map(_compile, SOURCES))
     tmp = LIB + f".tmp{os.getpid()}"
     subprocess.check_call([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])

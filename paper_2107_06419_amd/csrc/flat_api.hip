@@ -89,6 +89,41 @@ int flat_attn_unfused(const void* Q, const void* K, const void* V, void* O, int 
     return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
 }
 
+int flat_attn_tile_shape_count(int d) { return flat::tile_shape_count(d); }
+
+int flat_attn_tile_shape_get(int d, int index, flat_tile_shape* out) {
+    if (!out) return FLAT_ERR_NULL;
+    if (d != 64 && d != 128) return FLAT_ERR_UNSUPPORTED;
+    flat::TileShape t;
+    if (!flat::tile_shape(d, index, &t)) return FLAT_ERR_SHAPE;
+    out->d = t.d;
+    out->rows_per_workgroup = t.rows_per_workgroup;
+    out->keys_per_tile = t.keys_per_tile;
+    out->wavefronts = t.wavefronts;
+    out->rows_per_wavefront = t.rows_per_wavefront;
+    out->lds_stages = t.lds_stages;
+    out->lds_bytes = t.lds_bytes;
+    return FLAT_OK;
+}
+
+int flat_attn_tile_shape_occupancy(int d, int index) {
+    if (d != 64 && d != 128) return FLAT_ERR_UNSUPPORTED;
+    if (index < 0 || index >= flat::tile_shape_count(d)) return FLAT_ERR_SHAPE;
+    int n = 0;
+    return flat::tile_shape_occupancy(d, index, &n) == hipSuccess ? n : FLAT_ERR_HIP;
+}
+
+int flat_attn_fwd_tile(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
+                       int mask_kind, int tile_shape, void* stream) {
+    const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 2);
+    if (rc != FLAT_OK) return rc;
+    if ((unsigned long long)N * (unsigned)d * 2u > 0xffffffffULL) return FLAT_ERR_SHAPE;
+    if (tile_shape < 0 || tile_shape >= flat::tile_shape_count(d)) return FLAT_ERR_SHAPE;
+    const hipError_t e = flat::launch_fwd_bf16_tile(Q, K, V, O, B * H, N, d, scale, mask_kind == FLAT_MASK_CAUSAL, tile_shape,
+                                                    static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
+}
+
 size_t flat_attn_mfma_probe_sink_bytes(void) { return flat::mfma_probe_sink_bytes(); }
 
 double flat_attn_mfma_probe_flops(int iters) { return iters > 0 ? flat::mfma_probe_flops(iters) : 0.0; }

@@ -1,0 +1,528 @@
+// Fused attention forward for gfx950, bf16 in / fp32 accumulate / bf16 out.
+//
+// Dataflow (paper sections 4-5: fused Logit-softmax-Attend with a shared outer loop over batch,
+// head and blocks of query rows, the two inner loops interleaved):
+//   one workgroup = one (batch, head, block of BR query rows); its NW wavefronts own QW = BR/NW
+//   rows each.  The key/value sequence is streamed in tiles of 64 keys through a ring of LDS stages
+//   (the paper's double-buffered operand tiles, deepened to hide HBM/L2 latency).  Each tile is
+//   consumed as two blocks of 32 keys; per block a wavefront computes
+//       S^T = K_blk Q^T            (Logit, MFMA 32x32x16 bf16; the transposed product is chosen so
+//                                   that a lane owns ONE query column: row max / row sum are then
+//                                   in-lane reductions plus one exchange between wave halves)
+//       P   = exp2(c S - m)        (row softmax numerator against a reference max m, fp32 -> bf16 RNE)
+//       O^T += V_blk^T P^T         (Attend; the accumulator layout of S^T is already the B-operand
+//                                   layout of this product, so P never leaves registers;
+//                                   V^T operands come from ds_read_b64_tr_b16 on row-major V)
+// and only Q, K, V are read and O written: the N x N intermediate never exists off-chip.
+// Unlike the paper's row-granularity tile, which keeps a whole R x N logit slab on chip, the row
+// max and sum are carried as running values, so on-chip state is independent of N.
+//
+// Reference max and optimistic exponentiation.  softmax is invariant to the constant subtracted per
+// row, so m need not be the exact running maximum.  It starts as the (scaled) logit of key 0, which
+// every query sees, so the row sum is at least 1 relative to it and can never underflow.  The steady
+// state exponentiates against the current m WITHOUT computing the block maximum; a logit far above m
+// shows up as a jump of the fp32 row sum (more than kSumJump per lane and block, i.e. some
+// probability above 2^10), and only then the block takes the exact path: row maximum, raise m,
+// rescale O and l, recompute the block's probabilities.  Probabilities therefore stay below 2^14
+// relative to m, far inside bf16/fp32 range, and for typical data the exact path runs in the first
+// blocks only.
+#pragma once
+#include "flat_common.hpp"
+#include "flat_launch.hpp"
+
+namespace flat {
+
+constexpr float kSumJump = 16384.0f;  // per lane and 32-key block: 16 probabilities
+
+// LDS tile layout.  Rows are stored unpadded (ROWB = 2 D bytes) because tiles arrive by
+// global_load_lds_dwordx4, which writes the 64 lanes of a wavefront to 1024 contiguous LDS bytes
+// (lane l at base + 16 l).  Bank conflicts are avoided instead by an XOR swizzle of the 16-byte
+// chunk index within a row: chunk c of row r lives in slot c ^ swz(r).  The LDS serves 256 bytes
+// per clock: a ds_read_b128 touches 16 rows at one chunk index per clock, a ds_read_b64_tr_b16
+// touches 4 rows x 64 bytes; swz() is chosen so that both patterns hit every bank once.
+template <int D, int STAGES, int NW>
+struct Bf16Cfg {
+    static constexpr int BC = 64;                     // keys per tile
+    static constexpr int ROWB = D * 2;                // bytes per row
+    static constexpr int CHUNKS = ROWB / 16;          // 16-byte chunks per row
+    static constexpr int KBYTES = BC * ROWB;
+    static constexpr int VBYTES = BC * ROWB;
+    static constexpr int STAGE = KBYTES + VBYTES;
+    static constexpr int ROWS_PER_LOAD = 1024 / ROWB; // rows covered by one wave-wide 16-byte-per-lane load
+    static constexpr int LOADS = BC / ROWS_PER_LOAD / NW; // such loads per wavefront per tensor per tile
+    static constexpr int LDS_BYTES = STAGES * STAGE;
+    __device__ static __forceinline__ int swz(int r) {
+        if (D == 64) return (((r >> 1) & 1) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1);  // 128-byte rows: 2 rows per 256 B
+        return ((r & 3) << 2) | ((r >> 2) & 3);                                              // 256-byte rows
+    }
+};
+
+// One wave-wide global -> LDS copy, 16 bytes per lane: lane l's bytes land at lds_base + 16 l.
+// Issued as inline asm so that the compiler does not serialise later LDS reads of OTHER stages
+// behind it; completion is awaited explicitly with wait_vm<n>() before the stage is published by
+// a barrier.  lds_base must be wave-uniform.
+__device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(gbase) : "memory");
+}
+// s_waitcnt vmcnt(CNT) with the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4, lgkmcnt 11:8).  Emitted through the builtin so that the compiler's own wait bookkeeping
+// sees it.
+template <int CNT>
+__device__ __forceinline__ void wait_vm() {
+    static_assert(CNT >= 0 && CNT < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((CNT & 15) | ((CNT >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// Two wavefronts per SIMD (256 registers each), except 64 rows per wavefront at d = 128, whose accumulators alone
+// need more: that shape runs one wavefront per SIMD with the full 512 registers.
+template <int D, int QB, int NW, int STAGES, bool CAUSAL>
+__global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf16_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
+                                                          const bf16* __restrict__ V, bf16* __restrict__ O, int N,
+                                                          int n_qtiles, int n_blocks, int blocks_per_xcd, float c) {
+    using C = Bf16Cfg<D, STAGES, NW>;
+    constexpr int QW = 32 * QB, BR = NW * QW, BC = C::BC, DS = D / 16, DB = D / 32;
+    constexpr int LOADS_PER_TILE = 2 * C::LOADS;  // DMA instructions per wavefront per tile (K and V)
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    // Which (head, row block) this workgroup takes.  Workgroup ids are dealt round-robin to the 8 XCDs, so XCD x
+    // sees the ids x, x+8, ...: position t = id / 8 of its own sequence.
+    // Without a mask all blocks cost the same: XCD x takes the contiguous range [x, x+1) * blocks_per_xcd of
+    // (head, row block) pairs, so that the workgroups sharing one head's K/V share one L2.
+    // With the causal mask row block q costs ~ q+1 tiles, and the order decides the load balance.  All blocks are
+    // ranked heaviest first across ALL heads (rank g = rows-from-the-end * heads + head) and dealt to the XCDs
+    // like cards (XCD x gets ranks x, x+8, ...): every XCD gets the same mix, its late, dynamically placed
+    // workgroups are the light ones, and with a head count that is a multiple of 8 it still sees only its own
+    // heads.  When two workgroups fit a compute unit the hardware places positions t and t+32 of an XCD's
+    // sequence on the same unit in the first round; the second half of every 64 positions is therefore taken in
+    // reverse, which pairs the k-th heaviest of the 64 with the k-th lightest.
+    int bh, qt;
+    if (!CAUSAL) {
+        const int logical = xcd_logical_block(blockIdx.x, blocks_per_xcd);
+        if (logical >= n_blocks) return;
+        bh = logical / n_qtiles;
+        qt = logical - bh * n_qtiles;
+    } else {
+        constexpr int kByLds = (160 * 1024) / C::LDS_BYTES, kByRegs = 8 / NW;  // two wavefronts per SIMD
+        constexpr bool kTwoPerUnit = (kByLds < kByRegs ? kByLds : kByRegs) == 2;
+        const int x = blockIdx.x & 7, t = blockIdx.x >> 3;
+        int r = t;
+        if (kTwoPerUnit && (t | 63) < blocks_per_xcd && (t & 32)) r = (t & ~31) + 31 - (t & 31);
+        const int g = 8 * r + x;
+        if (g >= n_blocks) return;
+        const int heads = n_blocks / n_qtiles;
+        const int from_end = g / heads;
+        bh = g - from_end * heads;
+        qt = n_qtiles - 1 - from_end;
+    }
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const size_t head = (size_t)bh * N * D;
+    const bf16* Qh = Q + head;
+    const char* Kh = (const char*)(K + head);
+    const char* Vh = (const char*)(V + head);
+    bf16* Oh = O + head;
+    const int q0w = qt * BR + wave * QW;
+
+    // Q^T fragments (B operand of S^T = K Q^T): column = query, 8 consecutive head-dim elements
+    bf16x8 qf[QB][DS];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const int row = q0w + 32 * qb + l32;
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) {
+            uint4v z = {0, 0, 0, 0};
+            if (row < N) z = *(const uint4v*)(Qh + (size_t)row * D + ds * 16 + half * 8);
+            qf[qb][ds] = __builtin_bit_cast(bf16x8, z);
+        }
+    }
+
+    // reference max of each row = c * (q . k_0), from the fragments already in registers
+    float m[QB];
+    {
+        float k0[DS][8];
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) {
+            const uint4v kv = *(const uint4v*)(Kh + ds * 32 + half * 16);
+            const bf16x8 kb8 = __builtin_bit_cast(bf16x8, kv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) k0[ds][e] = (float)kb8[e];
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            float dot = 0.f;
+#pragma unroll
+            for (int ds = 0; ds < DS; ++ds)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot = __builtin_fmaf((float)qf[qb][ds][e], k0[ds][e], dot);
+            m[qb] = halves_sum(dot) * c;
+        }
+    }
+
+    floatx16 oacc[QB][DB];
+    float lsum[QB][2];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        lsum[qb][0] = lsum[qb][1] = 0.f;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[qb][db][r] = 0.f;
+    }
+
+    int kv_len = N;
+    if (CAUSAL) kv_len = min(N, qt * BR + BR);
+    const int n_tiles = (kv_len + BC - 1) / BC;
+
+    // ---- global -> LDS streaming.  Wave w issues load i of a tile for the 1024-byte LDS block
+    // (NW i + w); lane l fills slot (l % CHUNKS) of row (l / CHUNKS) of that block, so it fetches
+    // the chunk whose swizzled position that is.  Keys beyond N are clamped to the last key: their
+    // logits are masked and their (finite) values meet a zero probability.
+    const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
+    int ld_row[C::LOADS], ld_chunk_off[C::LOADS];
+#pragma unroll
+    for (int i = 0; i < C::LOADS; ++i) {
+        ld_row[i] = (NW * i + wave) * C::ROWS_PER_LOAD + lane / C::CHUNKS;
+        ld_chunk_off[i] = ((lane % C::CHUNKS) ^ C::swz(ld_row[i])) * 16;
+    }
+    auto issue_tile_loads = [&](int tile, int stage) __attribute__((always_inline)) {  // stage = tile % STAGES
+        const uint32_t stage_base = smem_base + (uint32_t)stage * C::STAGE;
+#pragma unroll
+        for (int i = 0; i < C::LOADS; ++i) {
+            const int key = min(tile * BC + ld_row[i], N - 1);
+            const uint32_t voff = (uint32_t)key * C::ROWB + ld_chunk_off[i];
+            const uint32_t lds_k = __builtin_amdgcn_readfirstlane(stage_base + (NW * i + wave) * 1024);
+            dma16(Kh, voff, lds_k);
+            dma16(Vh, voff, lds_k + C::KBYTES);
+        }
+    };
+
+    // per-lane LDS byte addresses of the MFMA operand reads (ring base + row part + swizzled chunk), one per
+    // compile-time chunk index
+    int koff[DS];
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) koff[ds] = (int)smem_base + l32 * C::ROWB + (((2 * ds + half) ^ C::swz(l32)) << 4);
+    const int i16 = lane & 15, g16 = lane >> 4;
+    int voff[DB][2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int hi = 0; hi < 2; ++hi) {
+            const int r = 8 * hi + 4 * (g16 >> 1) + (i16 >> 2);         // row within a 16-key step
+            const int ch = 4 * db + 2 * (g16 & 1) + ((i16 >> 1) & 1);  // 16-byte chunk holding this lane's 4 columns
+            voff[db][hi] = (int)smem_base + r * C::ROWB + ((ch ^ C::swz(r)) << 4) + (i16 & 1) * 8;
+        }
+    const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
+
+    // ---- block = 32 keys.  Pieces of the per-block work; the main loop below software-pipelines them so
+    // that the matrix pipe works on PV of block b-1 and on S of block b+1 while the vector ALU does the
+    // softmax of block b.
+    // (stage, kb) locate a block: ring stage of its tile and which half of the tile.  In the unrolled main loop
+    // both are compile-time constants and fold into the immediate offsets of the LDS reads.
+    auto read_k = [&](int stage, int kb, bf16x8 (&kf)[DS]) __attribute__((always_inline)) {  // K fragments (A operand of S^T = K Q^T) of one block
+        typedef const bf16x8 __attribute__((address_space(3))) * lds_frag_ptr;
+        const int block_off = stage * C::STAGE + kb * 32 * C::ROWB;
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) {
+            // Declaring the lane offset "modified" keeps (offset + constant) from being hoisted out of the loop
+            // into one register per stage; inside the loop the constant folds into the DS offset field.
+            asm volatile("" : "+v"(koff[ds]));
+            kf[ds] = *(lds_frag_ptr)(uintptr_t)(uint32_t)(koff[ds] + block_off);
+        }
+    };
+    auto read_v = [&](int stage, int kb, bf16x8 (&vf)[2][DB]) __attribute__((always_inline)) {  // V^T fragments (A operand of O^T += V^T P^T)
+        const int block_off = stage * C::STAGE + C::KBYTES + kb * 32 * C::ROWB;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            asm volatile("" : "+v"(voff[db][0]), "+v"(voff[db][1]));
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int off = block_off + t * 16 * C::ROWB;  // swz() only looks at row bits below 16
+                vf[t][db] = concat(lds_read_tr16_at(voff[db][0] + off), lds_read_tr16_at(voff[db][1] + off));
+            }
+        }
+    };
+    auto logits = [&](const bf16x8 (&kf)[DS], floatx16 (&x)[QB]) __attribute__((always_inline)) {  // S^T = K Q^T
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) x[qb][r] = 0.f;
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds)
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) x[qb] = mfma_bf16_32x32x16(kf[ds], qf[qb][ds], x[qb]);
+    };
+    auto attend = [&](const bf16x8 (&vf)[2][DB], const uint32_t (&p)[QB][8]) __attribute__((always_inline)) {  // O^T += V^T P^T
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    uint4v pw = {p[qb][4 * t], p[qb][4 * t + 1], p[qb][4 * t + 2], p[qb][4 * t + 3]};
+                    oacc[qb][db] = mfma_bf16_32x32x16(vf[t][db], __builtin_bit_cast(bf16x8, pw), oacc[qb][db]);
+                }
+    };
+    // x <- c S - m (masked keys -> -inf)
+    auto shift = [&](int blk, bool masked, floatx16 (&x)[QB]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float mref = m[qb];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) x[qb][r] = __builtin_fmaf(x[qb][r], c, -mref);
+            if (masked) {
+                const int qidx = q0w + 32 * qb + l32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = blk * 32 + acc_row(r, half);
+                    const bool ok = key < N && (!CAUSAL || key <= qidx);
+                    x[qb][r] = ok ? x[qb][r] : -INFINITY;  // exp2 -> probability exactly 0
+                }
+            }
+        }
+    };
+    auto row_max = [&](const floatx16 (&x)[QB], float (&mx)[QB]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            float a = x[qb][0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) a = __builtin_fmaxf(a, x[qb][r]);
+            mx[qb] = halves_max(a);
+        }
+    };
+    // p <- bf16(exp2(x)); bsum <- this block's sum of the ROUNDED probabilities (so that the row sum and the
+    // Attend operand agree), two partial sums per query block
+    auto softmax_b = [&](floatx16 (&x)[QB], uint32_t (&p)[QB][8], float (&bsum)[QB][2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            float l0 = 0.f, l1 = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; r += 4) {
+                float e[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) e[i] = __builtin_amdgcn_exp2f(x[qb][r + i]);
+                const uint32_t pk0 = pack_bf16(e[0], e[1]), pk1 = pack_bf16(e[2], e[3]);
+                p[qb][r >> 1] = pk0;
+                p[qb][(r >> 1) + 1] = pk1;
+                l0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0), ones, l0, false);
+                l1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1), ones, l1, false);
+            }
+            bsum[qb][0] = l0;
+            bsum[qb][1] = l1;
+        }
+    };
+    // Rare path: raise the reference max of every row whose block maximum lies above it, rescale O and l,
+    // and shift the block's exponents accordingly.
+    auto rescale = [&](floatx16 (&x)[QB], const float (&mx)[QB]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float delta = __builtin_fmaxf(mx[qb], 0.f);
+            const float alpha = __builtin_amdgcn_exp2f(-delta);
+            m[qb] += delta;
+            lsum[qb][0] *= alpha;
+            lsum[qb][1] *= alpha;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) x[qb][r] -= delta;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha;
+        }
+    };
+    // ---- prologue: fill STAGES-1 stages.  The full wait also retires the Q loads above, so that no
+    // wait on them is left inside the loops (it would drain the prefetch ring every iteration).
+#pragma unroll
+    for (int t = 0; t < STAGES - 1; ++t)
+        if (t < n_tiles) issue_tile_loads(t, t);
+    wait_vm<0>();
+    __syncthreads();
+
+    // With d = 128 two sets of V fragments do not fit the register file next to the accumulators: then one
+    // set is used, refilled in the middle of each step right after the MFMAs that consumed it were issued.
+    constexpr bool kTwoVSets = (D == 64);
+    // Pipeline state: xA/xB hold the logits of the current / next block, pA/pB and vfA/vfB the
+    // probabilities and V fragments of the block whose Attend is still owed.
+    floatx16 xA[QB], xB[QB];
+    uint32_t pA[QB][8], pB[QB][8];
+    bf16x8 vfA[2][DB], vfB[2][DB];  // vfB stays unused with one set
+    bf16x8 kf[DS];
+    float mx[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pB[qb][i] = 0u;  // the Attend owed before block 0 adds nothing
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) vfA[t][db] = vfB[t][db] = __builtin_bit_cast(bf16x8, (uint4v){0, 0, 0, 0});
+    read_k(0, 0, kf);
+    logits(kf, xA);
+
+    // One step = one block b:   matrix pipe: Attend(b-1) and S(b+1);   vector ALU: softmax(b).
+    // Stage bookkeeping (tile j = blocks 2j, 2j+1; reads of step b touch K of block b+1 and V of block b):
+    //   after step 2j   : wait for tile j+1, barrier  (also: every wave is past step 2j-1, the last reader of tile j-1)
+    //   before step 2j+1: start streaming tile j+STAGES-1 into the stage that held tile j-1
+    auto step = [&](int blk, int stage, int next_stage, bool masked, floatx16 (&xc)[QB], floatx16 (&xn)[QB], const uint32_t (&pp)[QB][8],
+                    const bf16x8 (&vp)[2][DB], uint32_t (&pc)[QB][8], bf16x8 (&vc)[2][DB]) __attribute__((always_inline)) {
+        read_k(next_stage, (blk + 1) & 1, kf);
+        if (kTwoVSets) read_v(stage, blk & 1, vc);
+        __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads at the top: they have a whole step to land
+        float bsum[QB][2];
+        constexpr int kMfmaPerStep = 2 * QB * DB + QB * DS, kValuPerMfma = (QB * 48) / kMfmaPerStep;
+        if (kTwoVSets) {
+            // one scheduling region: spread the MFMAs evenly through the softmax instructions
+            attend(vp, pp);
+            logits(kf, xn);
+            shift(blk, masked, xc);
+            softmax_b(xc, pc, bsum);
+#pragma unroll
+            for (int g = 0; g < kMfmaPerStep; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);             // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);  // its share of the vector work
+            }
+        } else {
+            // two regions; the single V fragment set (vp and vc are the same registers) is refilled between them
+            attend(vp, pp);
+            shift(blk, masked, xc);
+#pragma unroll
+            for (int g = 0; g < 2 * QB * DB; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, (QB * 16) / (2 * QB * DB), 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            read_v(stage, blk & 1, vc);
+            __builtin_amdgcn_sched_barrier(0);
+            logits(kf, xn);
+            softmax_b(xc, pc, bsum);
+#pragma unroll
+            for (int g = 0; g < QB * DS; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, (QB * 32) / (QB * DS), 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        bool jump = false;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) jump |= !(bsum[qb][0] + bsum[qb][1] <= kSumJump);
+        if (__builtin_amdgcn_ballot_w64(jump) != 0) {  // exact path: xc still holds c S - m of this block
+            row_max(xc, mx);
+            rescale(xc, mx);
+            softmax_b(xc, pc, bsum);
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            lsum[qb][0] += bsum[qb][0];
+            lsum[qb][1] += bsum[qb][1];
+        }
+    };
+    auto tile_steps = [&](int j, int sj, bool masked) __attribute__((always_inline)) {  // sj = j % STAGES
+        const int sn = sj + 1 == STAGES ? 0 : sj + 1;       // stage of tile j+1
+        const int sd = sj == 0 ? STAGES - 1 : sj - 1;       // stage of tile j-1 = target of tile j+STAGES-1
+        if (kTwoVSets)
+            step(2 * j, sj, sj, masked, xA, xB, pB, vfB, pA, vfA);
+        else
+            step(2 * j, sj, sj, masked, xA, xB, pB, vfA, pA, vfA);
+        if (j + STAGES - 2 < n_tiles)
+            wait_vm<(STAGES - 3) * LOADS_PER_TILE>();
+        else
+            wait_vm<0>();
+        __syncthreads();
+        if (j + STAGES - 1 < n_tiles) issue_tile_loads(j + STAGES - 1, sd);
+        if (kTwoVSets)
+            step(2 * j + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfB);
+        else
+            step(2 * j + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfA);
+    };
+
+    // Per wavefront the tiles fall into three consecutive ranges: fully visible, partly masked
+    // (sequence tail or causal diagonal), and not visible at all (the wavefront then only keeps
+    // streaming and synchronising for the others).
+    const int n_vis_blocks = (N + 31) / 32;
+    const int n_unm_tiles = (CAUSAL ? min(q0w / 32, N / 32) : N / 32) / 2;
+    const int n_act_tiles = ((CAUSAL ? min(n_vis_blocks, (q0w + QW) / 32) : n_vis_blocks) + 1) / 2;
+    int j = 0;
+    // main loop: STAGES fully visible tiles per trip, so that every ring stage index is a constant
+#pragma unroll 1
+    for (; j + STAGES <= n_unm_tiles; j += STAGES) {
+#pragma unroll
+        for (int sj = 0; sj < STAGES; ++sj) tile_steps(j + sj, sj, false);
+    }
+    // remaining visible tiles and the partly masked ones (masking a fully visible tile changes nothing)
+    int sj = 0;  // j is a multiple of STAGES here
+#pragma unroll 1
+    for (; j < n_act_tiles; ++j) {
+        tile_steps(j, sj, true);
+        sj = sj + 1 == STAGES ? 0 : sj + 1;
+    }
+    attend(kTwoVSets ? vfB : vfA, pB);  // the Attend still owed for the last block
+#pragma unroll 1
+    for (; j < n_tiles; ++j) {
+        if (j + STAGES - 2 < n_tiles)
+            wait_vm<(STAGES - 3) * LOADS_PER_TILE>();
+        else
+            wait_vm<0>();
+        __syncthreads();
+        if (j + STAGES - 1 < n_tiles) issue_tile_loads(j + STAGES - 1, sj == 0 ? STAGES - 1 : sj - 1);
+        sj = sj + 1 == STAGES ? 0 : sj + 1;
+    }
+
+    // ---- epilogue: O = O_acc / l, rounded to bf16; a lane holds 4 consecutive head-dim elements per register quad
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float inv = 1.0f / halves_sum(lsum[qb][0] + lsum[qb][1]);
+        const int row = q0w + 32 * qb + l32;
+        if (row < N) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    const int dcol = 32 * db + 8 * rq + 4 * half;
+                    floatx2 w;
+                    w[0] = __builtin_bit_cast(float, pack_bf16(oacc[qb][db][4 * rq] * inv, oacc[qb][db][4 * rq + 1] * inv));
+                    w[1] = __builtin_bit_cast(float, pack_bf16(oacc[qb][db][4 * rq + 2] * inv, oacc[qb][db][4 * rq + 3] * inv));
+                    *(floatx2*)(Oh + (size_t)row * D + dcol) = w;
+                }
+        }
+    }
+}
+
+template <int D, int QB, int NW, int STAGES, bool CAUSAL>
+inline hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* O, int BH, int N, float scale,
+                             hipStream_t stream) {
+    constexpr int BR = 32 * QB * NW;
+    const int n_qtiles = (N + BR - 1) / BR;
+    const int n_blocks = BH * n_qtiles;
+    const int blocks_per_xcd = (n_blocks + 7) / 8;
+    auto kern = fwd_bf16_kernel<D, QB, NW, STAGES, CAUSAL>;
+    constexpr int lds = Bf16Cfg<D, STAGES, NW>::LDS_BYTES;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(blocks_per_xcd * 8), dim3(64 * NW), lds, stream, (const bf16*)Q, (const bf16*)K,
+                       (const bf16*)V, (bf16*)O, N, n_qtiles, n_blocks, blocks_per_xcd, scale * kLog2e);
+    return hipGetLastError();
+}
+
+// The two mask variants of one tile shape behind one call; defined here, instantiated explicitly by the
+// translation units that own the shapes (declared in flat_launch.hpp).
+template <int D, int QB, int NW, int STAGES>
+hipError_t launch_fwd_bf16_shape(const void* Q, const void* K, const void* V, void* O, int BH, int N, float scale, int causal,
+                                 hipStream_t stream) {
+    return causal ? launch_cfg<D, QB, NW, STAGES, true>(Q, K, V, O, BH, N, scale, stream)
+                  : launch_cfg<D, QB, NW, STAGES, false>(Q, K, V, O, BH, N, scale, stream);
+}
+
+// Workgroups of this shape that fit one compute unit at a time (registers and LDS), as the runtime reports it.
+template <int D, int QB, int NW, int STAGES>
+hipError_t fwd_bf16_shape_occupancy(int* workgroups_per_cu) {
+    auto kern = fwd_bf16_kernel<D, QB, NW, STAGES, false>;
+    constexpr int lds = Bf16Cfg<D, STAGES, NW>::LDS_BYTES;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(workgroups_per_cu, kern, 64 * NW, lds);
+}
+
+#define FLAT_INSTANTIATE_BF16_SHAPE(D, QB, NW, STAGES)                                                                      \
+    template hipError_t launch_fwd_bf16_shape<D, QB, NW, STAGES>(const void*, const void*, const void*, void*, int, int, float, \
+                                                                 int, hipStream_t);                                        \
+    template hipError_t fwd_bf16_shape_occupancy<D, QB, NW, STAGES>(int*);
+
+}  // namespace flat

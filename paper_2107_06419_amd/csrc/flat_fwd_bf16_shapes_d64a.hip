@@ -1,0 +1,10 @@
+// Alternative tile shapes of the fused bf16 kernel, kept for the measured tile-shape sweep (table in flat_tiles.hip).
+#include "flat_fwd_bf16_kernel.hpp"
+
+namespace flat {
+
+FLAT_INSTANTIATE_BF16_SHAPE(64, 2, 4, 3)
+FLAT_INSTANTIATE_BF16_SHAPE(64, 2, 4, 6)
+FLAT_INSTANTIATE_BF16_SHAPE(64, 2, 8, 4)
+
+}  // namespace flat

@@ -9,6 +9,29 @@ namespace flat {
 hipError_t launch_fwd_bf16(const void* Q, const void* K, const void* V, void* O, int BH, int N, int d, float scale,
                            int causal, hipStream_t stream);
 
+// Tile shapes of the fused bf16 kernel (flat_tiles.hip).  Index 0 is the default of launch_fwd_bf16.
+struct TileShape {
+    int d;                   // head dimension the shape is built for
+    int rows_per_workgroup;  // query rows per workgroup
+    int keys_per_tile;       // keys per LDS stage
+    int wavefronts;          // wavefronts per workgroup
+    int rows_per_wavefront;
+    int lds_stages;          // depth of the K/V ring
+    int lds_bytes;           // dynamic LDS per workgroup
+};
+int tile_shape_count(int d);
+bool tile_shape(int d, int index, TileShape* out);
+hipError_t tile_shape_occupancy(int d, int index, int* workgroups_per_cu);
+hipError_t launch_fwd_bf16_tile(const void* Q, const void* K, const void* V, void* O, int BH, int N, int d, float scale,
+                                int causal, int index, hipStream_t stream);
+// One tile shape (D head dim, QB 32-row blocks per wavefront, NW wavefronts, STAGES ring depth): defined in
+// flat_fwd_bf16_kernel.hpp, instantiated by the flat_fwd_bf16*.hip translation units.
+template <int D, int QB, int NW, int STAGES>
+hipError_t launch_fwd_bf16_shape(const void* Q, const void* K, const void* V, void* O, int BH, int N, float scale, int causal,
+                                 hipStream_t stream);
+template <int D, int QB, int NW, int STAGES>
+hipError_t fwd_bf16_shape_occupancy(int* workgroups_per_cu);
+
 hipError_t launch_fwd_f32(const float* Q, const float* K, const float* V, float* O, int BH, int N, int d, float scale,
                           int causal, hipStream_t stream);
 

@@ -1,0 +1,67 @@
+// Table of the tile shapes the fused bf16 kernel is built for, and the dispatch by index.  Index 0 of each head
+// dimension is the shape flat_attn_fwd uses; the others exist so that the choice can be re-measured (the
+// paper's map-space exploration, section 6.1, done by timing instead of a cost model; the trade-off being
+// explored is the row granularity of section 5.3: fewer rows per workgroup re-fetch K and V more often and
+// fill the matrix units less, more rows need more on-chip state).
+#include "flat_launch.hpp"
+
+namespace flat {
+
+namespace {
+
+using LaunchFn = hipError_t (*)(const void*, const void*, const void*, void*, int, int, float, int, hipStream_t);
+using OccupancyFn = hipError_t (*)(int*);
+
+struct Entry {
+    TileShape shape;
+    LaunchFn launch;
+    OccupancyFn occupancy;
+};
+
+template <int D, int QB, int NW, int STAGES>
+constexpr Entry entry() {
+    return Entry{TileShape{D, 32 * QB * NW, 64, NW, 32 * QB, STAGES, STAGES * 2 * 64 * D * 2},
+                 &launch_fwd_bf16_shape<D, QB, NW, STAGES>, &fwd_bf16_shape_occupancy<D, QB, NW, STAGES>};
+}
+
+const Entry kD64[] = {entry<64, 2, 4, 4>(), entry<64, 2, 4, 3>(), entry<64, 2, 4, 6>(), entry<64, 2, 8, 4>(),
+                      entry<64, 1, 8, 4>(), entry<64, 1, 4, 4>(), entry<64, 2, 2, 4>()};
+const Entry kD128[] = {entry<128, 1, 8, 3>(), entry<128, 1, 8, 4>(), entry<128, 1, 4, 3>(), entry<128, 2, 4, 3>()};
+
+const Entry* find(int d, int index) {
+    if (index < 0 || index >= tile_shape_count(d)) return nullptr;
+    return d == 64 ? &kD64[index] : &kD128[index];
+}
+
+}  // namespace
+
+int tile_shape_count(int d) {
+    if (d == 64) return (int)(sizeof(kD64) / sizeof(kD64[0]));
+    if (d == 128) return (int)(sizeof(kD128) / sizeof(kD128[0]));
+    return 0;
+}
+
+bool tile_shape(int d, int index, TileShape* out) {
+    const Entry* e = find(d, index);
+    if (!e) return false;
+    *out = e->shape;
+    return true;
+}
+
+hipError_t tile_shape_occupancy(int d, int index, int* workgroups_per_cu) {
+    const Entry* e = find(d, index);
+    return e ? e->occupancy(workgroups_per_cu) : hipErrorInvalidValue;
+}
+
+hipError_t launch_fwd_bf16_tile(const void* Q, const void* K, const void* V, void* O, int BH, int N, int d, float scale,
+                                int causal, int index, hipStream_t stream) {
+    const Entry* e = find(d, index);
+    return e ? e->launch(Q, K, V, O, BH, N, scale, causal, stream) : hipErrorInvalidValue;
+}
+
+hipError_t launch_fwd_bf16(const void* Q, const void* K, const void* V, void* O, int BH, int N, int d, float scale,
+                           int causal, hipStream_t stream) {
+    return launch_fwd_bf16_tile(Q, K, V, O, BH, N, d, scale, causal, 0, stream);
+}
+
+}  // namespace flat

@@ -79,3 +79,35 @@ def test_validation_happens_before_any_gpu_work():
     assert unf(ws=0x8000004) == -4
     assert unf(ws=ok[3]) == -7
     assert unf(N=0) == -2
+
+
+def test_tile_shape_table_is_consistent():
+    """The shape table is host data: index 0 is the default, every entry describes a launchable shape, and
+    out-of-range queries are refused without touching a GPU."""
+    lib = fa.load_library()
+    assert fa.flat_attn_tile_shape_count(32) == 0 and fa.flat_attn_tile_shape_count(96) == 0
+    for d in (64, 128):
+        n = fa.flat_attn_tile_shape_count(d)
+        assert n >= 2
+        seen = set()
+        for idx in range(n):
+            t = fa.flat_attn_tile_shape_get(d, idx).as_dict()
+            assert t["d"] == d and t["keys_per_tile"] == 64
+            assert t["rows_per_workgroup"] == t["wavefronts"] * t["rows_per_wavefront"]
+            assert t["rows_per_wavefront"] in (32, 64) and 1 <= t["wavefronts"] <= 16
+            assert t["lds_stages"] >= 3
+            assert t["lds_bytes"] == t["lds_stages"] * 2 * t["keys_per_tile"] * d * 2 <= 160 * 1024  # K and V tiles, bf16
+            key = (t["rows_per_workgroup"], t["wavefronts"], t["lds_stages"])
+            assert key not in seen
+            seen.add(key)
+        for bad in (-1, n):
+            with pytest.raises(fa.FlatAttnError) as e:
+                fa.flat_attn_tile_shape_get(d, bad)
+            assert e.value.status == -2
+            assert lib.flat_attn_fwd_tile(0x1000, 1 << 40, 2 << 40, 3 << 40, 1, 1, 8, d, 1.0, 0, bad, None) == -2
+            assert lib.flat_attn_tile_shape_occupancy(d, bad) == -2
+    assert lib.flat_attn_tile_shape_get(64, 0, None) == -1
+    assert lib.flat_attn_tile_shape_occupancy(96, 0) == -3
+    d64, d128 = fa.flat_attn_tile_shape_get(64, 0).as_dict(), fa.flat_attn_tile_shape_get(128, 0).as_dict()
+    assert (d64["rows_per_workgroup"], d64["wavefronts"], d64["lds_stages"]) == (256, 4, 4)
+    assert (d128["rows_per_workgroup"], d128["wavefronts"], d128["lds_stages"]) == (256, 8, 3)

@@ -181,6 +181,29 @@ def test_unfused_workspace_holds_the_probabilities(N, mask):
     check_close(to_host_f64(out[:, :, torch.from_numpy(rows).cuda(), :]), oracle_rows(w, q, k, v, rows=rows), "bf16", w.name)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_every_tile_shape_matches_the_oracle(d):
+    """Each tile shape the library is built with is held to the same bar as the default one: a ragged length
+    spanning several workgroups and ring trips of the largest shape, with and without the causal mask, and the
+    degenerate one-key problem."""
+    import torch
+    import paper_2107_06419_amd as fa
+    count = fa.flat_attn_tile_shape_count(d)
+    assert count >= 2
+    for index in range(count):
+        shape = fa.flat_attn_tile_shape_get(d, index).as_dict()
+        assert fa.flat_attn_tile_shape_occupancy(d, index) >= 1
+        for N, mask in ((1, 0), (77, 1), (1500, 0), (1500, 1)):
+            w = synth.custom(f"tile_{d}_{index}_{N}_{mask}", 1, 2, N, d, "bf16", mask, seed=500 + 7 * index + N + mask)
+            q, k, v = synth.make_qkv(w)
+            dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+            out = torch.full_like(dq, float("nan"))
+            print(f"case tile shape {index} {shape} {w}", flush=True)
+            fa.flat_attn_fwd_tile(dq, dk, dv, out, w.scale, w.mask, index)
+            torch.cuda.synchronize()
+            check_close(to_host_f64(out), oracle_rows(w, q, k, v), "bf16", w.name)
+
+
 def test_status_codes_on_device_buffers():
     import torch
     import paper_2107_06419_amd as fa

@@ -60,8 +60,8 @@ __global__ __launch_bounds__(256) void logits_kernel(const bf16* __restrict__ Q,
 // ---------------------------------------------------------------------------------------------
 // 2. One workgroup per row; the row is replaced by exp(x - max) / sum.  Keys beyond the causal limit are
 //    written as exact zeros.  Two forms:
-//    - softmax_row_regs: rows of up to 256 * 4 * CH logits (N a multiple of 4) are held in registers, CH
-//      float4 per thread, so memory sees one read and one write of the row;
+//    - softmax_row_regs: rows of up to THREADS * 4 * CH logits (N a multiple of 4, at most 65536) are held in
+//      registers, CH float4 per thread, so memory sees one read and one write of the row;
 //    - softmax_row_stream: any N; a running (max, sum) pass and a second pass that reads the row again.
 __device__ __forceinline__ void online_combine(float& m, float& s, float m2, float s2) {
     const float mn = __builtin_fmaxf(m, m2);
@@ -71,7 +71,7 @@ __device__ __forceinline__ void online_combine(float& m, float& s, float m2, flo
     m = mn;
 }
 
-template <bool IS_MAX>
+template <bool IS_MAX, int WAVES>
 __device__ __forceinline__ float block_reduce(float v, float* slots) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -80,13 +80,16 @@ __device__ __forceinline__ float block_reduce(float v, float* slots) {
     }
     if ((threadIdx.x & 63) == 0) slots[threadIdx.x >> 6] = v;
     __syncthreads();
-    const float r0 = slots[0], r1 = slots[1], r2 = slots[2], r3 = slots[3];
-    return IS_MAX ? __builtin_fmaxf(__builtin_fmaxf(r0, r1), __builtin_fmaxf(r2, r3)) : (r0 + r1) + (r2 + r3);
+    float r = slots[0];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) r = IS_MAX ? __builtin_fmaxf(r, slots[w]) : r + slots[w];
+    return r;
 }
 
-template <bool CAUSAL, int CH>
-__global__ __launch_bounds__(256) void softmax_row_regs(float* __restrict__ L, int N) {
-    __shared__ float smax[4], ssum[4];
+template <bool CAUSAL, int CH, int THREADS>
+__global__ __launch_bounds__(THREADS) void softmax_row_regs(float* __restrict__ L, int N) {
+    constexpr int WAVES = THREADS / 64;
+    __shared__ float smax[WAVES], ssum[WAVES];
     const size_t rowid = blockIdx.x;  // bh * N + i
     const int i = (int)(rowid % (size_t)N);
     float* row = L + rowid * (size_t)N;
@@ -97,7 +100,7 @@ __global__ __launch_bounds__(256) void softmax_row_regs(float* __restrict__ L, i
     float m = -INFINITY;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-        const int j = (c * 256 + tid) * 4;
+        const int j = (c * THREADS + tid) * 4;
         x[c] = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
         if (j < nk) x[c] = *(const floatx4*)(row + j);  // j < nk <= N and N % 4 == 0, so j + 3 < N
 #pragma unroll
@@ -106,7 +109,7 @@ __global__ __launch_bounds__(256) void softmax_row_regs(float* __restrict__ L, i
             m = __builtin_fmaxf(m, x[c][e]);
         }
     }
-    m = block_reduce<true>(m, smax);  // key 0 is always valid, so m is finite
+    m = block_reduce<true, WAVES>(m, smax);  // key 0 is always valid, so m is finite
     float s = 0.f;
 #pragma unroll
     for (int c = 0; c < CH; ++c)
@@ -115,11 +118,11 @@ __global__ __launch_bounds__(256) void softmax_row_regs(float* __restrict__ L, i
             x[c][e] = __expf(x[c][e] - m);  // masked and out-of-row slots: exp(-inf) = 0
             s += x[c][e];
         }
-    s = block_reduce<false>(s, ssum);
+    s = block_reduce<false, WAVES>(s, ssum);
     const float inv = 1.0f / s;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-        const int j = (c * 256 + tid) * 4;
+        const int j = (c * THREADS + tid) * 4;
         if (j < N) *(floatx4*)(row + j) = floatx4{x[c][0] * inv, x[c][1] * inv, x[c][2] * inv, x[c][3] * inv};
     }
 }
@@ -163,15 +166,18 @@ __global__ __launch_bounds__(256) void softmax_row_stream(float* __restrict__ L,
 
 template <bool CAUSAL>
 static void launch_softmax(float* L, int BH, int N, hipStream_t stream) {
-    const dim3 grid((unsigned)((size_t)BH * N)), block(256);
-    if ((N & 3) == 0 && N <= 1024)
-        hipLaunchKernelGGL((softmax_row_regs<CAUSAL, 1>), grid, block, 0, stream, L, N);
-    else if ((N & 3) == 0 && N <= 4096)
-        hipLaunchKernelGGL((softmax_row_regs<CAUSAL, 4>), grid, block, 0, stream, L, N);
-    else if ((N & 3) == 0 && N <= 16384)
-        hipLaunchKernelGGL((softmax_row_regs<CAUSAL, 16>), grid, block, 0, stream, L, N);
+    const dim3 grid((unsigned)((size_t)BH * N));
+    const bool vec = (N & 3) == 0;
+    if (vec && N <= 1024)
+        hipLaunchKernelGGL((softmax_row_regs<CAUSAL, 1, 256>), grid, dim3(256), 0, stream, L, N);
+    else if (vec && N <= 4096)
+        hipLaunchKernelGGL((softmax_row_regs<CAUSAL, 4, 256>), grid, dim3(256), 0, stream, L, N);
+    else if (vec && N <= 16384)
+        hipLaunchKernelGGL((softmax_row_regs<CAUSAL, 16, 256>), grid, dim3(256), 0, stream, L, N);
+    else if (vec && N <= 65536)
+        hipLaunchKernelGGL((softmax_row_regs<CAUSAL, 16, 1024>), grid, dim3(1024), 0, stream, L, N);
     else
-        hipLaunchKernelGGL((softmax_row_stream<CAUSAL>), grid, block, 0, stream, L, N);
+        hipLaunchKernelGGL((softmax_row_stream<CAUSAL>), grid, dim3(256), 0, stream, L, N);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -43,6 +43,10 @@ def _load():
         lib.flat_oracle_attention.restype = ctypes.c_int
         lib.flat_oracle_attention.argtypes = [dp, dp, dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
                                               ctypes.c_double, ctypes.c_int, ip, ctypes.c_int64, ctypes.c_int]
+        lib.flat_oracle_attention_cross.restype = ctypes.c_int
+        lib.flat_oracle_attention_cross.argtypes = [dp, dp, dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                                    ctypes.c_int, ctypes.c_double, ctypes.c_int, ip, ip, ctypes.c_int64,
+                                                    ctypes.c_int]
         lib.flat_oracle_logits_softmax.restype = ctypes.c_int
         lib.flat_oracle_logits_softmax.argtypes = [dp, dp, ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_int,
                                                    ip, ctypes.c_int64, dp, dp]
@@ -84,6 +88,38 @@ def attention(Q, K, V, scale: float, mask_kind: int = 0, rows=None, threads: int
                                    rp, nr, int(threads))
     if rc != 0:
         raise ValueError(f"flat_oracle_attention rejected its arguments (code {rc})")
+    return O
+
+
+def attention_cross(Q, K, V, scale: float, mask_kind: int = 0, kv_lens=None, rows=None, threads: int = 0) -> np.ndarray:
+    """Attention of Q [B,H,Nq,d] over K, V [B,H,Nk,d] in float64 -> [B,H,len(rows) or Nq,d].
+
+    Causal: the queries are the last Nq positions of the key sequence (needs Nk >= Nq).  `kv_lens` (B
+    integers) limits batch entry b to its first kv_lens[b] keys.
+    """
+    lib = _load()
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    if Q.ndim != 4 or K.ndim != 4 or K.shape != V.shape or Q.shape[:2] != K.shape[:2] or Q.shape[3] != K.shape[3]:
+        raise ValueError("Q must be [B,H,Nq,d] and K, V [B,H,Nk,d]")
+    B, H, Nq, d = Q.shape
+    Nk = K.shape[2]
+    ip = ctypes.POINTER(ctypes.c_int64)
+    lp = None
+    if kv_lens is not None:
+        kv_lens = np.ascontiguousarray(kv_lens, dtype=np.int64)
+        if kv_lens.shape != (B,):
+            raise ValueError("kv_lens must hold one count per batch entry")
+        lp = kv_lens.ctypes.data_as(ip)
+    if rows is None:
+        rp, nr = None, Nq
+    else:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        rp, nr = rows.ctypes.data_as(ip), rows.size
+    O = np.empty((B, H, nr, d), dtype=np.float64)
+    rc = lib.flat_oracle_attention_cross(_dptr(Q), _dptr(K), _dptr(V), _dptr(O), B, H, Nq, Nk, d, float(scale), int(mask_kind),
+                                         lp, rp, nr, int(threads))
+    if rc != 0:
+        raise ValueError(f"flat_oracle_attention_cross rejected its arguments (code {rc})")
     return O
 
 

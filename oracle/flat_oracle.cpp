@@ -163,4 +163,66 @@ int flat_oracle_attention(const double* Q, const double* K, const double* V, dou
     return 0;
 }
 
+// Attention with Nq queries and Nk keys per head, for a set of query rows of every (batch, head).
+// The operators are those above; only the set of keys a query sees changes.  Readings (the paper does not
+// treat these cases; its workload list merely contains models that need them):
+//   * Q: [B,H,Nq,d], K, V: [B,H,Nk,d] doubles, O: [B,H,n_rows,d].
+//   * kv_lens (may be null): B counts; batch entry b uses its first kv_lens[b] keys (1 <= kv_lens[b] <= Nk), the
+//     remaining rows of K and V are padding with probability exactly 0.
+//   * mask_kind 1 (causal): the queries are the last Nq positions of the key sequence, so key j contributes to
+//     query i iff j <= i + (Nk - Nq); needs Nk >= Nq.  With kv_lens the alignment still refers to Nk.
+//   In every case the visible keys of a row are a prefix 0 .. n-1 of the key sequence, n >= 1.
+// Pins (tests/test_oracle_pins.py): equals flat_oracle_attention when Nq = Nk and kv_lens is null; the last Nq
+// rows of causal self-attention over Nk positions; attention over K, V truncated to kv_lens[b]; brute force
+// over explicit visibility tests on tiny shapes.
+int flat_oracle_attention_cross(const double* Q, const double* K, const double* V, double* O, int B, int H, int64_t Nq,
+                                int64_t Nk, int d, double scale, int mask_kind, const int64_t* kv_lens, const int64_t* rows,
+                                int64_t n_rows, int threads) {
+    if (!Q || !K || !V || !O || B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || d <= 0) return -1;
+    if (mask_kind != 0 && mask_kind != 1) return -3;
+    if (mask_kind == 1 && Nk < Nq) return -3;
+    if (kv_lens)
+        for (int b = 0; b < B; ++b)
+            if (kv_lens[b] < 1 || kv_lens[b] > Nk) return -2;
+    if (!rows) n_rows = Nq;
+    if (n_rows < 0) return -1;
+    if (rows)
+        for (int64_t r = 0; r < n_rows; ++r)
+            if (rows[r] < 0 || rows[r] >= Nq) return -2;
+    if (threads <= 0) threads = flat_oracle_hw_threads();
+
+    const int64_t n_items = (int64_t)B * H;
+    std::atomic<int64_t> next(0);
+    auto worker = [&]() {
+        std::vector<double> L(Nk), A(Nk);
+        for (;;) {
+            const int64_t bh = next.fetch_add(1);
+            if (bh >= n_items) break;
+            const int64_t len = kv_lens ? kv_lens[bh / H] : Nk;
+            const double* Qh = Q + bh * Nq * d;
+            const double* Kh = K + bh * Nk * d;
+            const double* Vh = V + bh * Nk * d;
+            for (int64_t r = 0; r < n_rows; ++r) {
+                const int64_t i = rows ? rows[r] : r;
+                int64_t n = len;
+                if (mask_kind == 1) {
+                    const int64_t last = i + (Nk - Nq);  // last key position this query may see
+                    n = last + 1 < len ? last + 1 : len;
+                }
+                logit_row(Qh + i * d, Kh, n, d, scale, L.data());
+                softmax_row(L.data(), n, A.data());
+                attend_row(A.data(), Vh, n, d, O + (bh * n_rows + r) * d);
+            }
+        }
+    };
+    if (threads == 1) {
+        worker();
+    } else {
+        std::vector<std::thread> pool;
+        for (int t = 0; t < threads; ++t) pool.emplace_back(worker);
+        for (auto& th : pool) th.join();
+    }
+    return 0;
+}
+
 }  // extern "C"

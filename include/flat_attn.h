@@ -45,7 +45,7 @@ typedef enum {
     FLAT_OK = 0,
     FLAT_ERR_NULL = -1,        /* a required pointer is NULL */
     FLAT_ERR_SHAPE = -2,       /* B, H or N is not positive, or B*H*N*N / B*H*N*d overflows */
-    FLAT_ERR_UNSUPPORTED = -3, /* d not in {64,128}, unknown mask_kind or dtype */
+    FLAT_ERR_UNSUPPORTED = -3, /* d not in {64,128}, unknown mask_kind or dtype, scale negative or not finite, causal with Nk < Nq */
     FLAT_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
     FLAT_ERR_WORKSPACE = -5,   /* workspace_bytes is smaller than flat_attn_unfused_workspace_bytes() */
     FLAT_ERR_HIP = -6,         /* the HIP runtime refused a launch */
@@ -65,6 +65,23 @@ typedef enum { FLAT_DTYPE_BF16 = 0 } flat_dtype;
  */
 int flat_attn_fwd(const void* Q, const void* K, const void* V, void* O,
                   int B, int H, int N, int d, float scale, int mask_kind, void* stream);
+
+/*
+ * The same kernel for queries and keys of different number, and for batches whose entries have different
+ * key counts.  The paper's workload list (section 6, "Workloads") has TransformerXL and T5 in it, models that
+ * attend over cached earlier segments or over another sequence, i.e. over more or other keys than queries; the
+ * dataflow of section 5 tiles the query rows and streams the keys, so only the loop bounds change.
+ *   Q: device, const bf16 [B,H,Nq,d].  K, V: device, const bf16 [B,H,Nk,d].  O: device, bf16 [B,H,Nq,d].
+ *   mask_kind FLAT_MASK_CAUSAL: the queries are the LAST Nq positions of the key sequence, i.e. key j
+ *     contributes to query i iff j <= i + (Nk - Nq); needs Nk >= Nq (else FLAT_ERR_UNSUPPORTED).
+ *   kv_lens: NULL, or device pointer to B ints (4-byte aligned, only read): batch entry b uses its first
+ *     kv_lens[b] keys, the rest of its Nk rows is padding with probability exactly 0.  Values are clamped to
+ *     [1, Nk] on the device; with the causal mask the alignment above still refers to Nk.
+ *   Nq = Nk, kv_lens = NULL gives exactly flat_attn_fwd.  One head of Q or K (N*d*2 bytes) must stay below 4 GiB.
+ */
+int flat_attn_fwd_cross(const void* Q, const void* K, const void* V, void* O,
+                        int B, int H, int Nq, int Nk, int d, float scale, int mask_kind,
+                        const int* kv_lens, void* stream);
 
 /*
  * Same dataflow in fp32 throughout (fp32 matrix instructions, fp32 probabilities).

@@ -55,6 +55,8 @@ def load_library():
     vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
     lib.flat_attn_fwd.restype = i
     lib.flat_attn_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, vp]
+    lib.flat_attn_fwd_cross.restype = i
+    lib.flat_attn_fwd_cross.argtypes = [vp, vp, vp, vp, i, i, i, i, i, f, i, vp, vp]
     lib.flat_attn_fwd_f32.restype = i
     lib.flat_attn_fwd_f32.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, vp]
     lib.flat_attn_unfused_workspace_bytes.restype = sz
@@ -123,6 +125,23 @@ def flat_attn_fwd(Q, K, V, O, scale: float, mask_kind: int = FLAT_MASK_NONE, str
     B, H, N, d = _dev_args(torch.bfloat16, Q, K, V, O)
     _check(load_library().flat_attn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
                                         float(scale), int(mask_kind), _stream_handle(stream)))
+
+
+def flat_attn_fwd_cross(Q, K, V, O, scale: float, mask_kind: int = FLAT_MASK_NONE, kv_lens=None, stream=None) -> None:
+    """Fused attention with Nq queries and Nk keys: Q, O bf16 [B,H,Nq,d], K, V bf16 [B,H,Nk,d] device tensors;
+    kv_lens: optional int32 device tensor of B key counts (padding beyond them is ignored)."""
+    import torch
+    B, H, Nq, d = _dev_args(torch.bfloat16, Q, O)
+    Bk, Hk, Nk, dk = _dev_args(torch.bfloat16, K, V)
+    if (Bk, Hk, dk) != (B, H, d):
+        raise ValueError("K, V must share batch, heads and head size with Q")
+    lens_ptr = None
+    if kv_lens is not None:
+        if not kv_lens.is_cuda or kv_lens.dtype != torch.int32 or not kv_lens.is_contiguous() or kv_lens.numel() != B:
+            raise ValueError("kv_lens must be a contiguous int32 GPU tensor with one entry per batch")
+        lens_ptr = kv_lens.data_ptr()
+    _check(load_library().flat_attn_fwd_cross(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, Nq, Nk, d,
+                                              float(scale), int(mask_kind), lens_ptr, _stream_handle(stream)))
 
 
 def flat_attn_fwd_f32(Q, K, V, O, scale: float, mask_kind: int = FLAT_MASK_NONE, stream=None) -> None:

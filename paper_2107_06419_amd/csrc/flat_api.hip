@@ -47,7 +47,35 @@ int flat_attn_fwd(const void* Q, const void* K, const void* V, void* O, int B, i
     const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 2);
     if (rc != FLAT_OK) return rc;
     if ((unsigned long long)N * (unsigned)d * 2u > 0xffffffffULL) return FLAT_ERR_SHAPE;  // the kernel addresses one head with 32-bit byte offsets
-    const hipError_t e = flat::launch_fwd_bf16(Q, K, V, O, B * H, N, d, scale, mask_kind == FLAT_MASK_CAUSAL,
+    const flat::Bf16Problem prob{N, N, 0, H, nullptr};
+    const hipError_t e = flat::launch_fwd_bf16(Q, K, V, O, B * H, prob, d, scale, mask_kind == FLAT_MASK_CAUSAL,
+                                               static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
+}
+
+int flat_attn_fwd_cross(const void* Q, const void* K, const void* V, void* O, int B, int H, int Nq, int Nk, int d, float scale,
+                        int mask_kind, const int* kv_lens, void* stream) {
+    // the checks of check_common, with separate lengths for the query side (Q, O) and the key side (K, V)
+    if (!Q || !K || !V || !O) return FLAT_ERR_NULL;
+    if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0) return FLAT_ERR_SHAPE;
+    if (d != 64 && d != 128) return FLAT_ERR_UNSUPPORTED;
+    if (mask_kind != FLAT_MASK_NONE && mask_kind != FLAT_MASK_CAUSAL) return FLAT_ERR_UNSUPPORTED;
+    if (!(scale >= 0.0f) || isinf(scale)) return FLAT_ERR_UNSUPPORTED;
+    if (mask_kind == FLAT_MASK_CAUSAL && Nk < Nq) return FLAT_ERR_UNSUPPORTED;  // some query would see no key
+    const long long BH = (long long)B * H;
+    if (BH > 0x7fffffffLL / ((Nq + 127) / 128)) return FLAT_ERR_SHAPE;
+    const unsigned long long per_head_q = (unsigned long long)Nq * (unsigned)d * 2u, per_head_k = (unsigned long long)Nk * (unsigned)d * 2u;
+    if (per_head_q > 0xffffffffULL || per_head_k > 0xffffffffULL) return FLAT_ERR_SHAPE;  // 32-bit byte offsets within a head
+    const unsigned __int128 qbytes128 = (unsigned __int128)BH * per_head_q, kbytes128 = (unsigned __int128)BH * per_head_k;
+    const unsigned __int128 lim = (unsigned __int128)1 << 62;
+    if (qbytes128 >= lim || kbytes128 >= lim) return FLAT_ERR_SHAPE;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return FLAT_ERR_ALIGN;
+    if (kv_lens && (reinterpret_cast<uintptr_t>(kv_lens) & 3u)) return FLAT_ERR_ALIGN;
+    const size_t qbytes = (size_t)qbytes128, kbytes = (size_t)kbytes128;
+    if (overlaps(O, qbytes, Q, qbytes) || overlaps(O, qbytes, K, kbytes) || overlaps(O, qbytes, V, kbytes)) return FLAT_ERR_ALIAS;
+    if (kv_lens && overlaps(O, qbytes, kv_lens, (size_t)B * sizeof(int))) return FLAT_ERR_ALIAS;
+    const flat::Bf16Problem prob{Nq, Nk, mask_kind == FLAT_MASK_CAUSAL ? Nk - Nq : 0, H, kv_lens};
+    const hipError_t e = flat::launch_fwd_bf16(Q, K, V, O, B * H, prob, d, scale, mask_kind == FLAT_MASK_CAUSAL,
                                                static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
 }
@@ -119,7 +147,8 @@ int flat_attn_fwd_tile(const void* Q, const void* K, const void* V, void* O, int
     if (rc != FLAT_OK) return rc;
     if ((unsigned long long)N * (unsigned)d * 2u > 0xffffffffULL) return FLAT_ERR_SHAPE;
     if (tile_shape < 0 || tile_shape >= flat::tile_shape_count(d)) return FLAT_ERR_SHAPE;
-    const hipError_t e = flat::launch_fwd_bf16_tile(Q, K, V, O, B * H, N, d, scale, mask_kind == FLAT_MASK_CAUSAL, tile_shape,
+    const flat::Bf16Problem prob{N, N, 0, H, nullptr};
+    const hipError_t e = flat::launch_fwd_bf16_tile(Q, K, V, O, B * H, prob, d, scale, mask_kind == FLAT_MASK_CAUSAL, tile_shape,
                                                     static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
 }
@@ -143,7 +172,8 @@ const char* flat_attn_status_string(int status) {
         case FLAT_OK: return "FLAT_OK";
         case FLAT_ERR_NULL: return "FLAT_ERR_NULL: a required pointer is NULL";
         case FLAT_ERR_SHAPE: return "FLAT_ERR_SHAPE: B, H or N not positive, or the problem is too large to index";
-        case FLAT_ERR_UNSUPPORTED: return "FLAT_ERR_UNSUPPORTED: d must be 64 or 128, mask_kind 0 or 1, scale finite and >= 0";
+        case FLAT_ERR_UNSUPPORTED:
+            return "FLAT_ERR_UNSUPPORTED: d must be 64 or 128, mask_kind 0 or 1, scale finite and >= 0, Nk >= Nq with the causal mask";
         case FLAT_ERR_ALIGN: return "FLAT_ERR_ALIGN: pointers must be 16-byte aligned";
         case FLAT_ERR_WORKSPACE: return "FLAT_ERR_WORKSPACE: workspace smaller than flat_attn_unfused_workspace_bytes()";
         case FLAT_ERR_HIP: return "FLAT_ERR_HIP: the HIP runtime refused a launch";

@@ -77,8 +77,9 @@ __device__ __forceinline__ void wait_vm() {
 // need more: that shape runs one wavefront per SIMD with the full 512 registers.
 template <int D, int QB, int NW, int STAGES, bool CAUSAL>
 __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf16_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
-                                                          const bf16* __restrict__ V, bf16* __restrict__ O, int N,
-                                                          int n_qtiles, int n_blocks, int blocks_per_xcd, float c) {
+                                                          const bf16* __restrict__ V, bf16* __restrict__ O,
+                                                          const Bf16Problem prob, int n_qtiles, int n_blocks,
+                                                          int blocks_per_xcd, float c) {
     using C = Bf16Cfg<D, STAGES, NW>;
     constexpr int QW = 32 * QB, BR = NW * QW, BC = C::BC, DS = D / 16, DB = D / 32;
     constexpr int LOADS_PER_TILE = 2 * C::LOADS;  // DMA instructions per wavefront per tile (K and V)
@@ -116,11 +117,16 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
     }
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
-    const size_t head = (size_t)bh * N * D;
-    const bf16* Qh = Q + head;
-    const char* Kh = (const char*)(K + head);
-    const char* Vh = (const char*)(V + head);
-    bf16* Oh = O + head;
+    // Nq query rows per head; N = number of keys of this head that count (the padded tail of a shorter batch
+    // entry is masked like the tail of a ragged tile); causal: query i sees keys 0 .. i + off.
+    const int Nq = prob.Nq, off = prob.causal_offset;
+    int N = prob.Nk;
+    if (prob.kv_lens) N = max(1, min(prob.Nk, prob.kv_lens[bh / prob.heads_per_batch]));
+    const size_t head_q = (size_t)bh * Nq * D, head_k = (size_t)bh * prob.Nk * D;
+    const bf16* Qh = Q + head_q;
+    const char* Kh = (const char*)(K + head_k);
+    const char* Vh = (const char*)(V + head_k);
+    bf16* Oh = O + head_q;
     const int q0w = qt * BR + wave * QW;
 
     // Q^T fragments (B operand of S^T = K Q^T): column = query, 8 consecutive head-dim elements
@@ -131,7 +137,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) {
             uint4v z = {0, 0, 0, 0};
-            if (row < N) z = *(const uint4v*)(Qh + (size_t)row * D + ds * 16 + half * 8);
+            if (row < Nq) z = *(const uint4v*)(Qh + (size_t)row * D + ds * 16 + half * 8);
             qf[qb][ds] = __builtin_bit_cast(bf16x8, z);
         }
     }
@@ -170,7 +176,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
     }
 
     int kv_len = N;
-    if (CAUSAL) kv_len = min(N, qt * BR + BR);
+    if (CAUSAL) kv_len = min(N, qt * BR + BR + off);
     const int n_tiles = (kv_len + BC - 1) / BC;
 
     // ---- global -> LDS streaming.  Wave w issues load i of a tile for the 1024-byte LDS block
@@ -274,7 +280,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int key = blk * 32 + acc_row(r, half);
-                    const bool ok = key < N && (!CAUSAL || key <= qidx);
+                    const bool ok = key < N && (!CAUSAL || key <= qidx + off);
                     x[qb][r] = ok ? x[qb][r] : -INFINITY;  // exp2 -> probability exactly 0
                 }
             }
@@ -437,8 +443,8 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
     // (sequence tail or causal diagonal), and not visible at all (the wavefront then only keeps
     // streaming and synchronising for the others).
     const int n_vis_blocks = (N + 31) / 32;
-    const int n_unm_tiles = (CAUSAL ? min(q0w / 32, N / 32) : N / 32) / 2;
-    const int n_act_tiles = ((CAUSAL ? min(n_vis_blocks, (q0w + QW) / 32) : n_vis_blocks) + 1) / 2;
+    const int n_unm_tiles = (CAUSAL ? min((q0w + off + 1) / 32, N / 32) : N / 32) / 2;
+    const int n_act_tiles = ((CAUSAL ? min(n_vis_blocks, (q0w + QW - 1 + off) / 32 + 1) : n_vis_blocks) + 1) / 2;
     int j = 0;
     // main loop: STAGES fully visible tiles per trip, so that every ring stage index is a constant
 #pragma unroll 1
@@ -470,7 +476,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
     for (int qb = 0; qb < QB; ++qb) {
         const float inv = 1.0f / halves_sum(lsum[qb][0] + lsum[qb][1]);
         const int row = q0w + 32 * qb + l32;
-        if (row < N) {
+        if (row < Nq) {
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -486,10 +492,10 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
 }
 
 template <int D, int QB, int NW, int STAGES, bool CAUSAL>
-inline hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* O, int BH, int N, float scale,
+inline hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, float scale,
                              hipStream_t stream) {
     constexpr int BR = 32 * QB * NW;
-    const int n_qtiles = (N + BR - 1) / BR;
+    const int n_qtiles = (prob.Nq + BR - 1) / BR;
     const int n_blocks = BH * n_qtiles;
     const int blocks_per_xcd = (n_blocks + 7) / 8;
     auto kern = fwd_bf16_kernel<D, QB, NW, STAGES, CAUSAL>;
@@ -497,17 +503,17 @@ inline hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* 
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(blocks_per_xcd * 8), dim3(64 * NW), lds, stream, (const bf16*)Q, (const bf16*)K,
-                       (const bf16*)V, (bf16*)O, N, n_qtiles, n_blocks, blocks_per_xcd, scale * kLog2e);
+                       (const bf16*)V, (bf16*)O, prob, n_qtiles, n_blocks, blocks_per_xcd, scale * kLog2e);
     return hipGetLastError();
 }
 
 // The two mask variants of one tile shape behind one call; defined here, instantiated explicitly by the
 // translation units that own the shapes (declared in flat_launch.hpp).
 template <int D, int QB, int NW, int STAGES>
-hipError_t launch_fwd_bf16_shape(const void* Q, const void* K, const void* V, void* O, int BH, int N, float scale, int causal,
-                                 hipStream_t stream) {
-    return causal ? launch_cfg<D, QB, NW, STAGES, true>(Q, K, V, O, BH, N, scale, stream)
-                  : launch_cfg<D, QB, NW, STAGES, false>(Q, K, V, O, BH, N, scale, stream);
+hipError_t launch_fwd_bf16_shape(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, float scale,
+                                 int causal, hipStream_t stream) {
+    return causal ? launch_cfg<D, QB, NW, STAGES, true>(Q, K, V, O, BH, prob, scale, stream)
+                  : launch_cfg<D, QB, NW, STAGES, false>(Q, K, V, O, BH, prob, scale, stream);
 }
 
 // Workgroups of this shape that fit one compute unit at a time (registers and LDS), as the runtime reports it.
@@ -521,8 +527,8 @@ hipError_t fwd_bf16_shape_occupancy(int* workgroups_per_cu) {
 }
 
 #define FLAT_INSTANTIATE_BF16_SHAPE(D, QB, NW, STAGES)                                                                      \
-    template hipError_t launch_fwd_bf16_shape<D, QB, NW, STAGES>(const void*, const void*, const void*, void*, int, int, float, \
-                                                                 int, hipStream_t);                                        \
+    template hipError_t launch_fwd_bf16_shape<D, QB, NW, STAGES>(const void*, const void*, const void*, void*, int,         \
+                                                                 const Bf16Problem&, float, int, hipStream_t);             \
     template hipError_t fwd_bf16_shape_occupancy<D, QB, NW, STAGES>(int*);
 
 }  // namespace flat

@@ -6,8 +6,17 @@
 
 namespace flat {
 
-hipError_t launch_fwd_bf16(const void* Q, const void* K, const void* V, void* O, int BH, int N, int d, float scale,
-                           int causal, hipStream_t stream);
+// Sequence geometry of one fused bf16 launch.  Self-attention is Nq = Nk, causal_offset = 0, kv_lens = null.
+struct Bf16Problem {
+    int Nq;               // query rows per head (Q and O are [B*H, Nq, d])
+    int Nk;               // key rows per head as laid out in memory (K and V are [B*H, Nk, d])
+    int causal_offset;    // causal mask: query i sees keys 0 .. i + causal_offset (>= 0)
+    int heads_per_batch;  // H, to find the batch entry of a head
+    const int* kv_lens;   // device, one int per batch entry: keys that count (the rest is padding), or null
+};
+
+hipError_t launch_fwd_bf16(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,
+                           float scale, int causal, hipStream_t stream);
 
 // Tile shapes of the fused bf16 kernel (flat_tiles.hip).  Index 0 is the default of launch_fwd_bf16.
 struct TileShape {
@@ -22,13 +31,13 @@ struct TileShape {
 int tile_shape_count(int d);
 bool tile_shape(int d, int index, TileShape* out);
 hipError_t tile_shape_occupancy(int d, int index, int* workgroups_per_cu);
-hipError_t launch_fwd_bf16_tile(const void* Q, const void* K, const void* V, void* O, int BH, int N, int d, float scale,
-                                int causal, int index, hipStream_t stream);
+hipError_t launch_fwd_bf16_tile(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,
+                                float scale, int causal, int index, hipStream_t stream);
 // One tile shape (D head dim, QB 32-row blocks per wavefront, NW wavefronts, STAGES ring depth): defined in
 // flat_fwd_bf16_kernel.hpp, instantiated by the flat_fwd_bf16*.hip translation units.
 template <int D, int QB, int NW, int STAGES>
-hipError_t launch_fwd_bf16_shape(const void* Q, const void* K, const void* V, void* O, int BH, int N, float scale, int causal,
-                                 hipStream_t stream);
+hipError_t launch_fwd_bf16_shape(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, float scale,
+                                 int causal, hipStream_t stream);
 template <int D, int QB, int NW, int STAGES>
 hipError_t fwd_bf16_shape_occupancy(int* workgroups_per_cu);
 

@@ -9,7 +9,7 @@ namespace flat {
 
 namespace {
 
-using LaunchFn = hipError_t (*)(const void*, const void*, const void*, void*, int, int, float, int, hipStream_t);
+using LaunchFn = hipError_t (*)(const void*, const void*, const void*, void*, int, const Bf16Problem&, float, int, hipStream_t);
 using OccupancyFn = hipError_t (*)(int*);
 
 struct Entry {
@@ -53,15 +53,15 @@ hipError_t tile_shape_occupancy(int d, int index, int* workgroups_per_cu) {
     return e ? e->occupancy(workgroups_per_cu) : hipErrorInvalidValue;
 }
 
-hipError_t launch_fwd_bf16_tile(const void* Q, const void* K, const void* V, void* O, int BH, int N, int d, float scale,
-                                int causal, int index, hipStream_t stream) {
+hipError_t launch_fwd_bf16_tile(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,
+                                float scale, int causal, int index, hipStream_t stream) {
     const Entry* e = find(d, index);
-    return e ? e->launch(Q, K, V, O, BH, N, scale, causal, stream) : hipErrorInvalidValue;
+    return e ? e->launch(Q, K, V, O, BH, prob, scale, causal, stream) : hipErrorInvalidValue;
 }
 
-hipError_t launch_fwd_bf16(const void* Q, const void* K, const void* V, void* O, int BH, int N, int d, float scale,
-                           int causal, hipStream_t stream) {
-    return launch_fwd_bf16_tile(Q, K, V, O, BH, N, d, scale, causal, 0, stream);
+hipError_t launch_fwd_bf16(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,
+                           float scale, int causal, hipStream_t stream) {
+    return launch_fwd_bf16_tile(Q, K, V, O, BH, prob, d, scale, causal, 0, stream);
 }
 
 }  // namespace flat

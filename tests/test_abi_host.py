@@ -111,3 +111,20 @@ def test_tile_shape_table_is_consistent():
     d64, d128 = fa.flat_attn_tile_shape_get(64, 0).as_dict(), fa.flat_attn_tile_shape_get(128, 0).as_dict()
     assert (d64["rows_per_workgroup"], d64["wavefronts"], d64["lds_stages"]) == (256, 4, 4)
     assert (d128["rows_per_workgroup"], d128["wavefronts"], d128["lds_stages"]) == (256, 8, 3)
+
+
+def test_cross_entry_point_validation():
+    lib = fa.load_library()
+    far = (0x1000, 1 << 40, 2 << 40, 3 << 40)
+
+    def cross(Q=far[0], K=far[1], V=far[2], O=far[3], B=1, H=1, Nq=8, Nk=16, d=64, scale=1.0, mask=0, lens=None):
+        return lib.flat_attn_fwd_cross(Q, K, V, O, B, H, Nq, Nk, d, scale, mask, lens, None)
+
+    assert cross(Q=None) == -1 and cross(O=None) == -1
+    assert cross(Nq=0) == -2 and cross(Nk=0) == -2 and cross(B=0) == -2
+    assert cross(d=80) == -3 and cross(mask=3) == -3 and cross(scale=float("nan")) == -3
+    assert cross(Nq=17, Nk=16, mask=1) == -3                 # causal: some query would see no key
+    assert cross(K=far[1] + 4) == -4 and cross(lens=0x5002) == -4
+    assert cross(O=far[1]) == -7 and cross(O=far[2] + 16) == -7
+    assert cross(lens=far[3] + 16) == -7                      # the key counts may not live inside O
+    assert cross(Nk=1 << 25, d=128) == -2 and cross(Nq=1 << 25, Nk=1 << 25, d=64) == -2

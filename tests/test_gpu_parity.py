@@ -204,6 +204,76 @@ def test_every_tile_shape_matches_the_oracle(d):
             check_close(to_host_f64(out), oracle_rows(w, q, k, v), "bf16", w.name)
 
 
+CROSS_CASES = [  # (B, H, Nq, Nk, kv_lens)
+    (1, 2, 1, 1, None), (2, 2, 1, 777, None), (1, 3, 100, 333, None), (2, 2, 300, 300, None), (1, 2, 640, 1700, None),
+    (3, 2, 257, 900, [900, 1, 413]), (2, 1, 1000, 1000, [64, 999]), (2, 2, 70, 2100, [2100, 1031]),
+]
+
+
+@pytest.mark.parametrize("B,H,Nq,Nk,lens", CROSS_CASES)
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("mask", [0, 1])
+def test_fused_cross_matches_oracle(B, H, Nq, Nk, lens, d, mask):
+    """Nq queries over Nk keys (one decoding step over a long cache, a segment over segment + memory, ragged
+    tails on both sides), with and without per-batch key counts; the padding rows hold huge values that must
+    not leak into the result."""
+    import torch
+    import paper_2107_06419_amd as fa
+    seed = 3000 + Nq + 3 * Nk + d + mask
+    scale = float(np.float32(d ** -0.5))
+    q = synth.tensor_f32((B, H, Nq, d), seed, 0, "normal", 1.0)
+    k = synth.tensor_f32((B, H, Nk, d), seed, 1, "normal", 1.0)
+    v = synth.tensor_f32((B, H, Nk, d), seed, 2, "normal", 1.0)
+    q, k, v = (synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(x)).reshape(x.shape) for x in (q, k, v))
+    kv_lens = None
+    if lens is not None:
+        for b, n in enumerate(lens):
+            k[b, :, n:, :] = 3.0e4
+            v[b, :, n:, :] = -3.0e4
+        kv_lens = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+    out = torch.full_like(dq, float("nan"))
+    print(f"case cross B={B} H={H} Nq={Nq} Nk={Nk} d={d} mask={mask} lens={lens}", flush=True)
+    fa.flat_attn_fwd_cross(dq, dk, dv, out, scale, mask, kv_lens)
+    torch.cuda.synchronize()
+    ref = oracle.attention_cross(q, k, v, scale, mask, kv_lens=None if lens is None else np.array(lens))
+    check_close(to_host_f64(out), ref, "bf16", "cross")
+
+
+def test_cross_with_equal_lengths_is_bitwise_the_self_attention_entry_point():
+    import torch
+    import paper_2107_06419_amd as fa
+    for d, mask in ((64, 0), (64, 1), (128, 1)):
+        w = synth.custom("eq", 2, 3, 1111, d, "bf16", mask, seed=17 + d)
+        q, k, v = synth.make_qkv(w)
+        dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+        a, b = torch.empty_like(dq), torch.empty_like(dq)
+        fa.flat_attn_fwd(dq, dk, dv, a, w.scale, w.mask)
+        fa.flat_attn_fwd_cross(dq, dk, dv, b, w.scale, w.mask, None)
+        torch.cuda.synchronize()
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_cross_long_cache_full_size_rows():
+    """A segment of 2048 queries over 32768 cached positions (d=64, causal): sampled rows against the oracle."""
+    import torch
+    import paper_2107_06419_amd as fa
+    B, H, Nq, Nk, d = 1, 8, 2048, 32768, 64
+    scale = 0.125
+    q = synth.tensor_f32((B, H, Nq, d), 991, 0, "normal", 1.0)
+    k = synth.tensor_f32((B, H, Nk, d), 991, 1, "normal", 1.0)
+    v = synth.tensor_f32((B, H, Nk, d), 991, 2, "normal", 1.0)
+    q, k, v = (synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(x)).reshape(x.shape) for x in (q, k, v))
+    dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+    out = torch.full_like(dq, float("nan"))
+    fa.flat_attn_fwd_cross(dq, dk, dv, out, scale, 1, None)
+    torch.cuda.synchronize()
+    rows = sample_rows(Nq, 24, seed=5)
+    ref = oracle.attention_cross(q, k, v, scale, 1, rows=rows)
+    check_close(to_host_f64(out[:, :, torch.from_numpy(rows).cuda(), :]), ref, "bf16", "cross long cache")
+    assert torch.isfinite(out.float()).all()
+
+
 def test_status_codes_on_device_buffers():
     import torch
     import paper_2107_06419_amd as fa

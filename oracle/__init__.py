@@ -47,6 +47,10 @@ def _load():
         lib.flat_oracle_attention_cross.argtypes = [dp, dp, dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
                                                     ctypes.c_int, ctypes.c_double, ctypes.c_int, ip, ip, ctypes.c_int64,
                                                     ctypes.c_int]
+        lib.flat_oracle_attention_blocksparse.restype = ctypes.c_int
+        lib.flat_oracle_attention_blocksparse.argtypes = [dp, dp, dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
+                                                          ctypes.c_double, ctypes.c_int64, ctypes.c_int64, ip, ip, ip,
+                                                          ctypes.c_int64, ctypes.c_int]
         lib.flat_oracle_logits_softmax.restype = ctypes.c_int
         lib.flat_oracle_logits_softmax.argtypes = [dp, dp, ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_int,
                                                    ip, ctypes.c_int64, dp, dp]
@@ -120,6 +124,37 @@ def attention_cross(Q, K, V, scale: float, mask_kind: int = 0, kv_lens=None, row
                                          lp, rp, nr, int(threads))
     if rc != 0:
         raise ValueError(f"flat_oracle_attention_cross rejected its arguments (code {rc})")
+    return O
+
+
+def attention_blocksparse(Q, K, V, scale: float, tile_offsets, tile_ids, block_rows: int = 256, block_keys: int = 64,
+                          rows=None, threads: int = 0) -> np.ndarray:
+    """Block-sparse attention in float64: query i sees key j iff tile j // block_keys is listed (CSR arrays
+    `tile_offsets`, `tile_ids`) for row block i // block_rows of its (batch, head).  [B,H,N,d] -> [B,H,len(rows) or N,d]."""
+    lib = _load()
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    if Q.ndim != 4 or Q.shape != K.shape or Q.shape != V.shape:
+        raise ValueError("Q, K, V must share a [B,H,N,d] shape")
+    B, H, N, d = Q.shape
+    ip = ctypes.POINTER(ctypes.c_int64)
+    offs = np.ascontiguousarray(tile_offsets, dtype=np.int64)
+    ids = np.ascontiguousarray(tile_ids, dtype=np.int64)
+    n_lists = B * H * ((N + block_rows - 1) // block_rows)
+    if offs.shape != (n_lists + 1,) or ids.ndim != 1 or (offs[-1] != ids.size):
+        raise ValueError("tile_offsets must have one entry per row block plus one and end at len(tile_ids)")
+    if ids.size == 0:
+        ids = np.zeros(1, dtype=np.int64)  # keeps the pointer valid; nothing is read
+    if rows is None:
+        rp, nr = None, N
+    else:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        rp, nr = rows.ctypes.data_as(ip), rows.size
+    O = np.empty((B, H, nr, d), dtype=np.float64)
+    rc = lib.flat_oracle_attention_blocksparse(_dptr(Q), _dptr(K), _dptr(V), _dptr(O), B, H, N, d, float(scale),
+                                               int(block_rows), int(block_keys), offs.ctypes.data_as(ip), ids.ctypes.data_as(ip),
+                                               rp, nr, int(threads))
+    if rc != 0:
+        raise ValueError(f"flat_oracle_attention_blocksparse rejected its arguments (code {rc})")
     return O
 
 

@@ -225,4 +225,85 @@ int flat_oracle_attention_cross(const double* Q, const double* K, const double* 
     return 0;
 }
 
+// Block-sparse attention: query i of a head sees key j iff tile j / block_keys is listed for the row block
+// i / block_rows of that head.  The operators are those above, applied to the visible keys only: they are
+// gathered (in ascending order) into contiguous K and V rows first.  Reading: the paper prunes the N x N matrix
+// randomly (section 8.2) without saying at what granularity; here the pattern is an input, at block granularity.
+//   tile_offsets: B*H*ceil(N/block_rows) + 1 counts (CSR); row block r = bh*ceil(N/block_rows) + i/block_rows owns
+//   tile_ids[tile_offsets[r] .. tile_offsets[r+1]), ids in [0, ceil(N/block_keys)), ascending and distinct.
+//   A row block with an empty list gives a zero row.  rows / n_rows / threads as in flat_oracle_attention.
+// Pins (tests/test_oracle_sparse_pins.py): every tile listed = flat_oracle_attention; the listed keys gathered by
+// the test = flat_oracle_attention_cross over them; a prefix of tiles = truncated K, V; brute force over an explicit
+// per-pair visibility test.
+int flat_oracle_attention_blocksparse(const double* Q, const double* K, const double* V, double* O, int B, int H, int64_t N,
+                                      int d, double scale, int64_t block_rows, int64_t block_keys,
+                                      const int64_t* tile_offsets, const int64_t* tile_ids, const int64_t* rows,
+                                      int64_t n_rows, int threads) {
+    if (!Q || !K || !V || !O || !tile_offsets || !tile_ids || B <= 0 || H <= 0 || N <= 0 || d <= 0) return -1;
+    if (block_rows <= 0 || block_keys <= 0) return -1;
+    const int64_t n_rb = (N + block_rows - 1) / block_rows, n_kt = (N + block_keys - 1) / block_keys;
+    const int64_t n_lists = (int64_t)B * H * n_rb;
+    if (tile_offsets[0] != 0) return -2;
+    for (int64_t r = 0; r < n_lists; ++r) {
+        if (tile_offsets[r + 1] < tile_offsets[r]) return -2;
+        for (int64_t e = tile_offsets[r]; e < tile_offsets[r + 1]; ++e) {
+            if (tile_ids[e] < 0 || tile_ids[e] >= n_kt) return -2;
+            if (e > tile_offsets[r] && tile_ids[e] <= tile_ids[e - 1]) return -2;
+        }
+    }
+    if (!rows) n_rows = N;
+    if (n_rows < 0) return -1;
+    if (rows)
+        for (int64_t r = 0; r < n_rows; ++r)
+            if (rows[r] < 0 || rows[r] >= N) return -2;
+    if (threads <= 0) threads = flat_oracle_hw_threads();
+
+    const int64_t n_items = (int64_t)B * H;
+    std::atomic<int64_t> next(0);
+    auto worker = [&]() {
+        std::vector<double> L(N), A(N), Kg((size_t)N * d), Vg((size_t)N * d);
+        for (;;) {
+            const int64_t bh = next.fetch_add(1);
+            if (bh >= n_items) break;
+            const double* Qh = Q + bh * N * d;
+            const double* Kh = K + bh * N * d;
+            const double* Vh = V + bh * N * d;
+            int64_t gathered_for = -1, n = 0;  // row block whose keys Kg, Vg hold
+            for (int64_t r = 0; r < n_rows; ++r) {
+                const int64_t i = rows ? rows[r] : r;
+                const int64_t rb = bh * n_rb + i / block_rows;
+                if (rb != gathered_for) {
+                    n = 0;
+                    for (int64_t e = tile_offsets[rb]; e < tile_offsets[rb + 1]; ++e) {
+                        const int64_t j0 = tile_ids[e] * block_keys;
+                        const int64_t j1 = j0 + block_keys < N ? j0 + block_keys : N;
+                        for (int64_t j = j0; j < j1; ++j, ++n)
+                            for (int c = 0; c < d; ++c) {
+                                Kg[n * d + c] = Kh[j * d + c];
+                                Vg[n * d + c] = Vh[j * d + c];
+                            }
+                    }
+                    gathered_for = rb;
+                }
+                double* O_row = O + (bh * n_rows + r) * d;
+                if (n == 0) {
+                    for (int c = 0; c < d; ++c) O_row[c] = 0.0;
+                    continue;
+                }
+                logit_row(Qh + i * d, Kg.data(), n, d, scale, L.data());
+                softmax_row(L.data(), n, A.data());
+                attend_row(A.data(), Vg.data(), n, d, O_row);
+            }
+        }
+    };
+    if (threads == 1) {
+        worker();
+    } else {
+        std::vector<std::thread> pool;
+        for (int t = 0; t < threads; ++t) pool.emplace_back(worker);
+        for (auto& th : pool) th.join();
+    }
+    return 0;
+}
+
 }  // extern "C"

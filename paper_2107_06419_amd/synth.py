@@ -163,3 +163,20 @@ def custom(name: str, B: int, H: int, N: int, d: int, dtype: str = "bf16", mask:
     if scale is None:
         scale = 1.0 / float(np.sqrt(float(d)))
     return Workload(name, B, H, N, d, dtype, mask, _f32(scale), qk_mult, v_dist, seed)
+
+
+def random_block_pattern(n_lists: int, n_key_tiles: int, keep: float, seed: int, at_least_one: bool = True):
+    """Seeded random block pattern in CSR form: for each of `n_lists` row blocks, every key tile is kept with
+    probability `keep` (counter-based: tile t of list r depends on (seed, r, t) only).  Returns (offsets int64
+    [n_lists + 1], ids int64, ascending within a list).  With `at_least_one`, an otherwise empty list keeps tile
+    (r mod n_key_tiles)."""
+    u = tensor_f32((n_lists, n_key_tiles), seed, 7, "uniform", 1.0)  # uniform in [-1, 1)
+    kept = (u.astype(np.float64) + 1.0) * 0.5 < keep
+    if at_least_one:
+        for r in np.flatnonzero(~kept.any(axis=1)):
+            kept[r, r % n_key_tiles] = True
+    counts = kept.sum(axis=1)
+    offsets = np.zeros(n_lists + 1, dtype=np.int64)
+    np.cumsum(counts, out=offsets[1:])
+    ids = np.nonzero(kept)[1].astype(np.int64)
+    return offsets, ids

@@ -84,6 +84,26 @@ int flat_attn_fwd_cross(const void* Q, const void* K, const void* V, void* O,
                         const int* kv_lens, void* stream);
 
 /*
+ * Block-sparse variant.  The paper asks (section 8.2, compatibility with sparse-attention accelerators) whether
+ * the Logit/Attend pair stays worth fusing when the N x N matrix is pruned, and prunes it randomly at 50 %.  On
+ * this hardware pruning pays only at the granularity the kernel works at, so the pattern is given in blocks of
+ * FLAT_SPARSE_BLOCK_ROWS query rows x FLAT_SPARSE_BLOCK_KEYS keys: query i sees key j iff tile j / 64 is listed
+ * for row block i / 256 of its (batch, head).  Unlisted tiles are neither loaded nor computed.
+ *   Q, K, V, O: as flat_attn_fwd (self-attention, N <= 131072).  No causal form.
+ *   tile_offsets: device, B*H*ceil(N/256) + 1 ints, only read: row block r = (b*H + h)*ceil(N/256) + i/256 owns
+ *     tile_ids[tile_offsets[r] .. tile_offsets[r+1]).
+ *   tile_ids: device, n_tile_ids ints in [0, ceil(N/64)), ascending and distinct within a row block.
+ *   The lists live on the device and are not validated by the host: out-of-range offsets and ids are clamped
+ *     (never a stray access), duplicate or unsorted ids give a wrong result.  A row block with an empty list
+ *     produces zeros.  Listing every tile for every row block reproduces flat_attn_fwd bit for bit.
+ */
+#define FLAT_SPARSE_BLOCK_ROWS 256
+#define FLAT_SPARSE_BLOCK_KEYS 64
+int flat_attn_fwd_blocksparse(const void* Q, const void* K, const void* V, void* O,
+                              int B, int H, int N, int d, float scale,
+                              const int* tile_offsets, const int* tile_ids, int n_tile_ids, void* stream);
+
+/*
  * Same dataflow in fp32 throughout (fp32 matrix instructions, fp32 probabilities).
  *   Q, K, V: device, const float [B,H,N,d].  O: device, float [B,H,N,d].
  */

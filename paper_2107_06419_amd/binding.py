@@ -57,6 +57,8 @@ def load_library():
     lib.flat_attn_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, vp]
     lib.flat_attn_fwd_cross.restype = i
     lib.flat_attn_fwd_cross.argtypes = [vp, vp, vp, vp, i, i, i, i, i, f, i, vp, vp]
+    lib.flat_attn_fwd_blocksparse.restype = i
+    lib.flat_attn_fwd_blocksparse.argtypes = [vp, vp, vp, vp, i, i, i, i, f, vp, vp, i, vp]
     lib.flat_attn_fwd_f32.restype = i
     lib.flat_attn_fwd_f32.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, vp]
     lib.flat_attn_unfused_workspace_bytes.restype = sz
@@ -142,6 +144,26 @@ def flat_attn_fwd_cross(Q, K, V, O, scale: float, mask_kind: int = FLAT_MASK_NON
         lens_ptr = kv_lens.data_ptr()
     _check(load_library().flat_attn_fwd_cross(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, Nq, Nk, d,
                                               float(scale), int(mask_kind), lens_ptr, _stream_handle(stream)))
+
+
+FLAT_SPARSE_BLOCK_ROWS = 256
+FLAT_SPARSE_BLOCK_KEYS = 64
+
+
+def flat_attn_fwd_blocksparse(Q, K, V, O, scale: float, tile_offsets, tile_ids, stream=None) -> None:
+    """Block-sparse fused attention: int32 device tensors `tile_offsets` (B*H*ceil(N/256) + 1) and `tile_ids` list,
+    per block of 256 query rows, the 64-key tiles it sees (CSR, ids ascending)."""
+    import torch
+    B, H, N, d = _dev_args(torch.bfloat16, Q, K, V, O)
+    for t in (tile_offsets, tile_ids):
+        if not t.is_cuda or t.dtype != torch.int32 or not t.is_contiguous():
+            raise ValueError("tile_offsets and tile_ids must be contiguous int32 GPU tensors")
+    n_row_blocks = B * H * ((N + FLAT_SPARSE_BLOCK_ROWS - 1) // FLAT_SPARSE_BLOCK_ROWS)
+    if tile_offsets.numel() != n_row_blocks + 1:
+        raise ValueError(f"tile_offsets must have {n_row_blocks + 1} entries")
+    _check(load_library().flat_attn_fwd_blocksparse(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
+                                                    float(scale), tile_offsets.data_ptr(), tile_ids.data_ptr(),
+                                                    int(tile_ids.numel()), _stream_handle(stream)))
 
 
 def flat_attn_fwd_f32(Q, K, V, O, scale: float, mask_kind: int = FLAT_MASK_NONE, stream=None) -> None:

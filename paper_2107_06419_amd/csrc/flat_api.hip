@@ -47,7 +47,7 @@ int flat_attn_fwd(const void* Q, const void* K, const void* V, void* O, int B, i
     const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 2);
     if (rc != FLAT_OK) return rc;
     if ((unsigned long long)N * (unsigned)d * 2u > 0xffffffffULL) return FLAT_ERR_SHAPE;  // the kernel addresses one head with 32-bit byte offsets
-    const flat::Bf16Problem prob{N, N, 0, H, nullptr};
+    const flat::Bf16Problem prob{N, N, 0, H, nullptr, nullptr, nullptr, 0};
     const hipError_t e = flat::launch_fwd_bf16(Q, K, V, O, B * H, prob, d, scale, mask_kind == FLAT_MASK_CAUSAL,
                                                static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
@@ -74,7 +74,7 @@ int flat_attn_fwd_cross(const void* Q, const void* K, const void* V, void* O, in
     const size_t qbytes = (size_t)qbytes128, kbytes = (size_t)kbytes128;
     if (overlaps(O, qbytes, Q, qbytes) || overlaps(O, qbytes, K, kbytes) || overlaps(O, qbytes, V, kbytes)) return FLAT_ERR_ALIAS;
     if (kv_lens && overlaps(O, qbytes, kv_lens, (size_t)B * sizeof(int))) return FLAT_ERR_ALIAS;
-    const flat::Bf16Problem prob{Nq, Nk, mask_kind == FLAT_MASK_CAUSAL ? Nk - Nq : 0, H, kv_lens};
+    const flat::Bf16Problem prob{Nq, Nk, mask_kind == FLAT_MASK_CAUSAL ? Nk - Nq : 0, H, kv_lens, nullptr, nullptr, 0};
     const hipError_t e = flat::launch_fwd_bf16(Q, K, V, O, B * H, prob, d, scale, mask_kind == FLAT_MASK_CAUSAL,
                                                static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
@@ -117,6 +117,24 @@ int flat_attn_unfused(const void* Q, const void* K, const void* V, void* O, int 
     return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
 }
 
+int flat_attn_fwd_blocksparse(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
+                              const int* tile_offsets, const int* tile_ids, int n_tile_ids, void* stream) {
+    const int rc = check_common(Q, K, V, O, B, H, N, d, scale, FLAT_MASK_NONE, 2);
+    if (rc != FLAT_OK) return rc;
+    if (!tile_offsets || !tile_ids) return FLAT_ERR_NULL;
+    if (N > FLAT_SPARSE_BLOCK_KEYS * 2048) return FLAT_ERR_SHAPE;  // a row block's list must fit its LDS copy
+    if (n_tile_ids < 0) return FLAT_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(tile_offsets) & 3u) || (reinterpret_cast<uintptr_t>(tile_ids) & 3u)) return FLAT_ERR_ALIGN;
+    const size_t tbytes = (size_t)B * H * N * d * 2;
+    const size_t n_row_blocks = (size_t)B * H * ((N + FLAT_SPARSE_BLOCK_ROWS - 1) / FLAT_SPARSE_BLOCK_ROWS);
+    if (overlaps(O, tbytes, tile_offsets, (n_row_blocks + 1) * sizeof(int)) ||
+        (n_tile_ids > 0 && overlaps(O, tbytes, tile_ids, (size_t)n_tile_ids * sizeof(int))))
+        return FLAT_ERR_ALIAS;
+    const flat::Bf16Problem prob{N, N, 0, H, nullptr, tile_offsets, tile_ids, n_tile_ids};
+    const hipError_t e = flat::launch_fwd_bf16_sparse(Q, K, V, O, B * H, prob, d, scale, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
+}
+
 int flat_attn_tile_shape_count(int d) { return flat::tile_shape_count(d); }
 
 int flat_attn_tile_shape_get(int d, int index, flat_tile_shape* out) {
@@ -147,7 +165,7 @@ int flat_attn_fwd_tile(const void* Q, const void* K, const void* V, void* O, int
     if (rc != FLAT_OK) return rc;
     if ((unsigned long long)N * (unsigned)d * 2u > 0xffffffffULL) return FLAT_ERR_SHAPE;
     if (tile_shape < 0 || tile_shape >= flat::tile_shape_count(d)) return FLAT_ERR_SHAPE;
-    const flat::Bf16Problem prob{N, N, 0, H, nullptr};
+    const flat::Bf16Problem prob{N, N, 0, H, nullptr, nullptr, nullptr, 0};
     const hipError_t e = flat::launch_fwd_bf16_tile(Q, K, V, O, B * H, prob, d, scale, mask_kind == FLAT_MASK_CAUSAL, tile_shape,
                                                     static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;

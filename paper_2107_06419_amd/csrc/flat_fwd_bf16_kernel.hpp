@@ -75,7 +75,11 @@ __device__ __forceinline__ void wait_vm() {
 
 // Two wavefronts per SIMD (256 registers each), except 64 rows per wavefront at d = 128, whose accumulators alone
 // need more: that shape runs one wavefront per SIMD with the full 512 registers.
-template <int D, int QB, int NW, int STAGES, bool CAUSAL>
+// SPARSE: block-sparse variant.  The workgroup visits only the 64-key tiles listed for its row block (ids in
+// ascending order, staged in LDS behind the ring); everything else is as in the dense kernel.
+constexpr int kMaxSparseTiles = 2048;  // listed tiles per row block that fit the LDS list (8 KiB)
+
+template <int D, int QB, int NW, int STAGES, bool CAUSAL, bool SPARSE = false>
 __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf16_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                           const bf16* __restrict__ V, bf16* __restrict__ O,
                                                           const Bf16Problem prob, int n_qtiles, int n_blocks,
@@ -96,6 +100,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
     // heads.  When two workgroups fit a compute unit the hardware places positions t and t+32 of an XCD's
     // sequence on the same unit in the first round; the second half of every 64 positions is therefore taken in
     // reverse, which pairs the k-th heaviest of the 64 with the k-th lightest.
+    static_assert(!(CAUSAL && SPARSE), "the block-sparse variant has no causal form");
     int bh, qt;
     if (!CAUSAL) {
         const int logical = xcd_logical_block(blockIdx.x, blocks_per_xcd);
@@ -142,13 +147,30 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
         }
     }
 
-    // reference max of each row = c * (q . k_0), from the fragments already in registers
+    // Block-sparse: copy this row block's tile list into LDS (ids forced into range; a wrong list can give a
+    // wrong result but no stray access).
+    int* const sp_ids = (int*)(smem + C::LDS_BYTES);
+    int sp_count = 0;
+    if (SPARSE) {
+        const int n_ktiles = (N + BC - 1) / BC;
+        const int row_block = bh * n_qtiles + qt;
+        const int lo = max(0, min(prob.n_tile_ids, prob.tile_offsets[row_block]));
+        const int hi = max(lo, min(prob.n_tile_ids, prob.tile_offsets[row_block + 1]));
+        sp_count = min(hi - lo, kMaxSparseTiles);
+        for (int i = tid; i < sp_count; i += 64 * NW) sp_ids[i] = max(0, min(n_ktiles - 1, prob.tile_ids[lo + i]));
+        __syncthreads();
+    }
+    auto tile_of = [&](int j) __attribute__((always_inline)) { return SPARSE ? sp_ids[j] : j; };  // j-th tile this workgroup visits
+
+    // reference max of each row = c * (q . k_first), k_first = the first key the row block sees (key 0 unless
+    // block-sparse), from the fragments already in registers
     float m[QB];
     {
         float k0[DS][8];
+        const int first_key = (SPARSE && sp_count > 0) ? sp_ids[0] * BC : 0;
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) {
-            const uint4v kv = *(const uint4v*)(Kh + ds * 32 + half * 16);
+            const uint4v kv = *(const uint4v*)(Kh + (size_t)first_key * C::ROWB + ds * 32 + half * 16);
             const bf16x8 kb8 = __builtin_bit_cast(bf16x8, kv);
 #pragma unroll
             for (int e = 0; e < 8; ++e) k0[ds][e] = (float)kb8[e];
@@ -177,7 +199,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
 
     int kv_len = N;
     if (CAUSAL) kv_len = min(N, qt * BR + BR + off);
-    const int n_tiles = (kv_len + BC - 1) / BC;
+    const int n_tiles = SPARSE ? sp_count : (kv_len + BC - 1) / BC;  // tiles this workgroup visits
 
     // ---- global -> LDS streaming.  Wave w issues load i of a tile for the 1024-byte LDS block
     // (NW i + w); lane l fills slot (l % CHUNKS) of row (l / CHUNKS) of that block, so it fetches
@@ -190,8 +212,9 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
         ld_row[i] = (NW * i + wave) * C::ROWS_PER_LOAD + lane / C::CHUNKS;
         ld_chunk_off[i] = ((lane % C::CHUNKS) ^ C::swz(ld_row[i])) * 16;
     }
-    auto issue_tile_loads = [&](int tile, int stage) __attribute__((always_inline)) {  // stage = tile % STAGES
+    auto issue_tile_loads = [&](int j, int stage) __attribute__((always_inline)) {  // j-th visited tile, stage = j % STAGES
         const uint32_t stage_base = smem_base + (uint32_t)stage * C::STAGE;
+        const int tile = tile_of(j);
 #pragma unroll
         for (int i = 0; i < C::LOADS; ++i) {
             const int key = min(tile * BC + ld_row[i], N - 1);
@@ -423,10 +446,12 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
     auto tile_steps = [&](int j, int sj, bool masked) __attribute__((always_inline)) {  // sj = j % STAGES
         const int sn = sj + 1 == STAGES ? 0 : sj + 1;       // stage of tile j+1
         const int sd = sj == 0 ? STAGES - 1 : sj - 1;       // stage of tile j-1 = target of tile j+STAGES-1
+        // first 32-key block of the tile, as a key position / 32 (only the masked form of a step looks at it)
+        const int kb0 = 2 * ((SPARSE && masked) ? tile_of(j) : j);
         if (kTwoVSets)
-            step(2 * j, sj, sj, masked, xA, xB, pB, vfB, pA, vfA);
+            step(kb0, sj, sj, masked, xA, xB, pB, vfB, pA, vfA);
         else
-            step(2 * j, sj, sj, masked, xA, xB, pB, vfA, pA, vfA);
+            step(kb0, sj, sj, masked, xA, xB, pB, vfA, pA, vfA);
         if (j + STAGES - 2 < n_tiles)
             wait_vm<(STAGES - 3) * LOADS_PER_TILE>();
         else
@@ -434,17 +459,18 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
         __syncthreads();
         if (j + STAGES - 1 < n_tiles) issue_tile_loads(j + STAGES - 1, sd);
         if (kTwoVSets)
-            step(2 * j + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfB);
+            step(kb0 + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfB);
         else
-            step(2 * j + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfA);
+            step(kb0 + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfA);
     };
 
     // Per wavefront the tiles fall into three consecutive ranges: fully visible, partly masked
     // (sequence tail or causal diagonal), and not visible at all (the wavefront then only keeps
     // streaming and synchronising for the others).
     const int n_vis_blocks = (N + 31) / 32;
-    const int n_unm_tiles = (CAUSAL ? min((q0w + off + 1) / 32, N / 32) : N / 32) / 2;
-    const int n_act_tiles = ((CAUSAL ? min(n_vis_blocks, (q0w + QW - 1 + off) / 32 + 1) : n_vis_blocks) + 1) / 2;
+    // (block-sparse: the list is ascending, so only its last tile can be the ragged end of the sequence)
+    const int n_unm_tiles = SPARSE ? max(n_tiles - 1, 0) : (CAUSAL ? min((q0w + off + 1) / 32, N / 32) : N / 32) / 2;
+    const int n_act_tiles = SPARSE ? n_tiles : ((CAUSAL ? min(n_vis_blocks, (q0w + QW - 1 + off) / 32 + 1) : n_vis_blocks) + 1) / 2;
     int j = 0;
     // main loop: STAGES fully visible tiles per trip, so that every ring stage index is a constant
 #pragma unroll 1
@@ -474,7 +500,8 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
     // ---- epilogue: O = O_acc / l, rounded to bf16; a lane holds 4 consecutive head-dim elements per register quad
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const float inv = 1.0f / halves_sum(lsum[qb][0] + lsum[qb][1]);
+        const float total = halves_sum(lsum[qb][0] + lsum[qb][1]);
+        const float inv = (SPARSE && n_tiles == 0) ? 0.f : 1.0f / total;  // a row block with an empty list yields zeros
         const int row = q0w + 32 * qb + l32;
         if (row < Nq) {
 #pragma unroll
@@ -491,15 +518,15 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
     }
 }
 
-template <int D, int QB, int NW, int STAGES, bool CAUSAL>
+template <int D, int QB, int NW, int STAGES, bool CAUSAL, bool SPARSE = false>
 inline hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, float scale,
                              hipStream_t stream) {
     constexpr int BR = 32 * QB * NW;
     const int n_qtiles = (prob.Nq + BR - 1) / BR;
     const int n_blocks = BH * n_qtiles;
     const int blocks_per_xcd = (n_blocks + 7) / 8;
-    auto kern = fwd_bf16_kernel<D, QB, NW, STAGES, CAUSAL>;
-    constexpr int lds = Bf16Cfg<D, STAGES, NW>::LDS_BYTES;
+    auto kern = fwd_bf16_kernel<D, QB, NW, STAGES, CAUSAL, SPARSE>;
+    constexpr int lds = Bf16Cfg<D, STAGES, NW>::LDS_BYTES + (SPARSE ? kMaxSparseTiles * (int)sizeof(int) : 0);
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(blocks_per_xcd * 8), dim3(64 * NW), lds, stream, (const bf16*)Q, (const bf16*)K,
@@ -524,6 +551,13 @@ hipError_t fwd_bf16_shape_occupancy(int* workgroups_per_cu) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(workgroups_per_cu, kern, 64 * NW, lds);
+}
+
+// Block-sparse launch of one tile shape (its row block is the shape's rows per workgroup).
+template <int D, int QB, int NW, int STAGES>
+hipError_t launch_fwd_bf16_sparse_shape(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob,
+                                        float scale, hipStream_t stream) {
+    return launch_cfg<D, QB, NW, STAGES, false, true>(Q, K, V, O, BH, prob, scale, stream);
 }
 
 #define FLAT_INSTANTIATE_BF16_SHAPE(D, QB, NW, STAGES)                                                                      \

@@ -13,10 +13,17 @@ struct Bf16Problem {
     int causal_offset;    // causal mask: query i sees keys 0 .. i + causal_offset (>= 0)
     int heads_per_batch;  // H, to find the batch entry of a head
     const int* kv_lens;   // device, one int per batch entry: keys that count (the rest is padding), or null
+    // block-sparse launches only (else null / 0): CSR list of the 64-key tiles each 256-row block visits
+    const int* tile_offsets;  // device, B*H*ceil(Nq/256) + 1 ints
+    const int* tile_ids;      // device, n_tile_ids ints
+    int n_tile_ids;
 };
 
 hipError_t launch_fwd_bf16(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,
                            float scale, int causal, hipStream_t stream);
+
+hipError_t launch_fwd_bf16_sparse(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,
+                                  float scale, hipStream_t stream);
 
 // Tile shapes of the fused bf16 kernel (flat_tiles.hip).  Index 0 is the default of launch_fwd_bf16.
 struct TileShape {

@@ -128,3 +128,17 @@ def test_cross_entry_point_validation():
     assert cross(O=far[1]) == -7 and cross(O=far[2] + 16) == -7
     assert cross(lens=far[3] + 16) == -7                      # the key counts may not live inside O
     assert cross(Nk=1 << 25, d=128) == -2 and cross(Nq=1 << 25, Nk=1 << 25, d=64) == -2
+
+
+def test_blocksparse_entry_point_validation():
+    lib = fa.load_library()
+    far = (0x1000, 1 << 40, 2 << 40, 3 << 40)
+
+    def sp(Q=far[0], K=far[1], V=far[2], O=far[3], B=1, H=1, N=512, d=64, scale=1.0, offs=0x9000, ids=0xA000, n=4):
+        return lib.flat_attn_fwd_blocksparse(Q, K, V, O, B, H, N, d, scale, offs, ids, n, None)
+
+    assert sp(Q=None) == -1 and sp(offs=None) == -1 and sp(ids=None) == -1
+    assert sp(N=0) == -2 and sp(N=131072 + 1) == -2 and sp(n=-1) == -2
+    assert sp(d=96) == -3 and sp(scale=-1.0) == -3
+    assert sp(offs=0x9002) == -4 and sp(ids=0xA001) == -4 and sp(V=far[2] + 8) == -4
+    assert sp(O=far[0]) == -7 and sp(offs=far[3] + 64) == -7 and sp(ids=far[3] + 128) == -7

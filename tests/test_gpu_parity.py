@@ -274,6 +274,69 @@ def test_cross_long_cache_full_size_rows():
     assert torch.isfinite(out.float()).all()
 
 
+def _run_blocksparse(w, q, k, v, offs, ids):
+    import torch
+    import paper_2107_06419_amd as fa
+    dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+    out = torch.full_like(dq, float("nan"))
+    d_offs = torch.from_numpy(offs.astype(np.int32)).cuda()
+    d_ids = torch.from_numpy((ids if ids.size else np.zeros(1, dtype=np.int64)).astype(np.int32)).cuda()[:ids.size]
+    fa.flat_attn_fwd_blocksparse(dq, dk, dv, out, w.scale, d_offs, d_ids)
+    torch.cuda.synchronize()
+    return out
+
+
+@pytest.mark.parametrize("B,H,N", [(1, 1, 1), (1, 2, 64), (2, 2, 257), (1, 3, 1000), (2, 2, 2304), (1, 2, 5000)])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("keep", [0.5, 0.1])
+def test_fused_blocksparse_matches_oracle(B, H, N, d, keep):
+    """Random block patterns (256 rows x 64 keys) at 50 % and 10 % density, ragged lengths, several row blocks
+    per head and ring trips; the oracle gets the same lists."""
+    w = synth.custom(f"sparse_{N}_{d}", B, H, N, d, "bf16", 0, seed=700 + N + d)
+    q, k, v = synth.make_qkv(w)
+    n_rb, n_kt = -(-N // 256), -(-N // 64)
+    offs, ids = synth.random_block_pattern(B * H * n_rb, n_kt, keep, seed=N + d + int(100 * keep))
+    print(f"case blocksparse {w} keep={keep} listed={ids.size} of {B * H * n_rb * n_kt}", flush=True)
+    out = _run_blocksparse(w, q, k, v, offs, ids)
+    ref = oracle.attention_blocksparse(q, k, v, w.scale, offs, ids)
+    check_close(to_host_f64(out), ref, "bf16", w.name)
+
+
+def test_blocksparse_with_every_tile_is_bitwise_the_dense_kernel_and_empty_lists_give_zeros():
+    import torch
+    import paper_2107_06419_amd as fa
+    for d in (64, 128):
+        w = synth.custom("sparse_full", 2, 2, 1500, d, "bf16", 0, seed=41 + d)
+        q, k, v = synth.make_qkv(w)
+        n_rb, n_kt = -(-w.N // 256), -(-w.N // 64)
+        n_lists = w.B * w.H * n_rb
+        offs = np.arange(n_lists + 1, dtype=np.int64) * n_kt
+        ids = np.tile(np.arange(n_kt, dtype=np.int64), n_lists)
+        out = _run_blocksparse(w, q, k, v, offs, ids)
+        dense = run_entry("fused", w, q, k, v)
+        assert torch.equal(out.view(torch.int16), dense.view(torch.int16))
+        # row block 1 of every head sees nothing, the others only tile 3
+        counts = np.ones(n_lists, dtype=np.int64)
+        counts[1::n_rb] = 0
+        offs = np.concatenate([[0], np.cumsum(counts)])
+        ids = np.full(int(counts.sum()), 3, dtype=np.int64)
+        out = _run_blocksparse(w, q, k, v, offs, ids)
+        assert (out[:, :, 256:512, :].float() == 0).all()
+        ref = oracle.attention_blocksparse(q, k, v, w.scale, offs, ids)
+        check_close(to_host_f64(out), ref, "bf16", "sparse with empty lists")
+
+
+def test_blocksparse_lists_out_of_range_are_clamped_not_followed():
+    """Garbage lists must not fault: offsets and ids outside their ranges are forced into them on the device."""
+    import torch
+    w = synth.custom("sparse_bad", 1, 2, 700, 64, "bf16", 0, seed=3)
+    q, k, v = synth.make_qkv(w)
+    offs = np.array([0, 5, -7, 1 << 30, 2, 9, 9], dtype=np.int64)    # 2 heads x 3 row blocks + 1
+    ids = np.array([0, 1 << 20, -5, 3, 10, 2, 2, 7, 11], dtype=np.int64)
+    out = _run_blocksparse(w, q, k, v, offs, ids)
+    assert out.shape == (1, 2, 700, 64)     # completed; values are unspecified for invalid lists
+
+
 def test_status_codes_on_device_buffers():
     import torch
     import paper_2107_06419_amd as fa

@@ -187,10 +187,10 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
     }
 
     floatx16 oacc[QB][DB];
-    float lsum[QB][2];
+    float lsum[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        lsum[qb][0] = lsum[qb][1] = 0.f;
+        lsum[qb] = 0.f;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -319,11 +319,12 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
         }
     };
     // p <- bf16(exp2(x)); bsum <- this block's sum of the ROUNDED probabilities (so that the row sum and the
-    // Attend operand agree), two partial sums per query block
-    auto softmax_b = [&](floatx16 (&x)[QB], uint32_t (&p)[QB][8], float (&bsum)[QB][2]) __attribute__((always_inline)) {
+    // Attend operand agree).  One accumulator chain per query block: its links are spread through the step
+    // anyway, and a second chain costs more in merging than it gains.
+    auto softmax_b = [&](floatx16 (&x)[QB], uint32_t (&p)[QB][8], float (&bsum)[QB]) __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            float l0 = 0.f, l1 = 0.f;
+            float l0 = 0.f;
 #pragma unroll
             for (int r = 0; r < 16; r += 4) {
                 float e[4];
@@ -333,10 +334,9 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
                 p[qb][r >> 1] = pk0;
                 p[qb][(r >> 1) + 1] = pk1;
                 l0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0), ones, l0, false);
-                l1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1), ones, l1, false);
+                l0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1), ones, l0, false);
             }
-            bsum[qb][0] = l0;
-            bsum[qb][1] = l1;
+            bsum[qb] = l0;
         }
     };
     // Rare path: raise the reference max of every row whose block maximum lies above it, rescale O and l,
@@ -347,8 +347,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
             const float delta = __builtin_fmaxf(mx[qb], 0.f);
             const float alpha = __builtin_amdgcn_exp2f(-delta);
             m[qb] += delta;
-            lsum[qb][0] *= alpha;
-            lsum[qb][1] *= alpha;
+            lsum[qb] *= alpha;
 #pragma unroll
             for (int r = 0; r < 16; ++r) x[qb][r] -= delta;
 #pragma unroll
@@ -395,7 +394,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
         read_k(next_stage, (blk + 1) & 1, kf);
         if (kTwoVSets) read_v(stage, blk & 1, vc);
         __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads at the top: they have a whole step to land
-        float bsum[QB][2];
+        float bsum[QB];
         constexpr int kMfmaPerStep = 2 * QB * DB + QB * DS, kValuPerMfma = (QB * 48) / kMfmaPerStep;
         if (kTwoVSets) {
             // one scheduling region: spread the MFMAs evenly through the softmax instructions
@@ -431,7 +430,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
         __builtin_amdgcn_sched_barrier(0);
         bool jump = false;
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) jump |= !(bsum[qb][0] + bsum[qb][1] <= kSumJump);
+        for (int qb = 0; qb < QB; ++qb) jump |= !(bsum[qb] <= kSumJump);
         if (__builtin_amdgcn_ballot_w64(jump) != 0) {  // exact path: xc still holds c S - m of this block
             row_max(xc, mx);
             rescale(xc, mx);
@@ -439,8 +438,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
         }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            lsum[qb][0] += bsum[qb][0];
-            lsum[qb][1] += bsum[qb][1];
+            lsum[qb] += bsum[qb];
         }
     };
     auto tile_steps = [&](int j, int sj, bool masked) __attribute__((always_inline)) {  // sj = j % STAGES
@@ -500,7 +498,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
     // ---- epilogue: O = O_acc / l, rounded to bf16; a lane holds 4 consecutive head-dim elements per register quad
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const float total = halves_sum(lsum[qb][0] + lsum[qb][1]);
+        const float total = halves_sum(lsum[qb]);
         const float inv = (SPARSE && n_tiles == 0) ? 0.f : 1.0f / total;  // a row block with an empty list yields zeros
         const int row = q0w + 32 * qb + l32;
         if (row < Nq) {

@@ -6,5 +6,6 @@ namespace flat {
 FLAT_INSTANTIATE_BF16_SHAPE(64, 1, 8, 4)
 FLAT_INSTANTIATE_BF16_SHAPE(64, 1, 4, 4)
 FLAT_INSTANTIATE_BF16_SHAPE(64, 2, 2, 4)
+FLAT_INSTANTIATE_BF16_SHAPE(64, 1, 4, 3)
 
 }  // namespace flat

@@ -25,7 +25,7 @@ constexpr Entry entry() {
 }
 
 const Entry kD64[] = {entry<64, 2, 4, 4>(), entry<64, 2, 4, 3>(), entry<64, 2, 4, 6>(), entry<64, 2, 8, 4>(),
-                      entry<64, 1, 8, 4>(), entry<64, 1, 4, 4>(), entry<64, 2, 2, 4>()};
+                      entry<64, 1, 8, 4>(), entry<64, 1, 4, 4>(), entry<64, 2, 2, 4>(), entry<64, 1, 4, 3>()};
 const Entry kD128[] = {entry<128, 1, 8, 3>(), entry<128, 1, 8, 4>(), entry<128, 1, 4, 3>(), entry<128, 2, 4, 3>()};
 
 const Entry* find(int d, int index) {

@@ -1,7 +1,7 @@
 // Fused attention forward for gfx950 in fp32 throughout (fp32 MFMA 32x32x2, fp32 probabilities).
 // Same dataflow as the bf16 kernel (paper sections 4-5: one pass over blocks of query rows with
 // Logit, softmax and Attend interleaved), sized for small problems: 4 wavefronts x 32 query rows
-// per workgroup, 32 keys per tile, single LDS stage.
+// per workgroup, 32 keys per tile, one LDS stage fed from a register prefetch of the next tile.
 #include "flat_common.hpp"
 #include "flat_launch.hpp"
 
@@ -45,25 +45,40 @@ __global__ __launch_bounds__(256) void fwd_f32_kernel(const float* __restrict__ 
     if (CAUSAL) kv_len = min(N, qt * BR + BR);
     const int n_tiles = (kv_len + BC - 1) / BC;
 
+    // K/V tiles are fetched one tile ahead into registers and written to LDS once the previous tile's readers
+    // are done, so the global-memory latency overlaps the MFMAs of the tile before.
+    constexpr int LD = BC * D / 4 / 256;  // float4 loads per thread, tile and tensor
+    floatx4 kreg[LD], vreg[LD];
+    auto fetch_tile = [&](int jbase) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < LD; ++i) {
+            const int ch = tid + 256 * i;
+            const int row = ch / (D / 4), col = (ch % (D / 4)) * 4;
+            kreg[i] = floatx4{0, 0, 0, 0};
+            vreg[i] = floatx4{0, 0, 0, 0};
+            if (jbase + row < N) {
+                kreg[i] = *(const floatx4*)(Kh + (size_t)(jbase + row) * D + col);
+                vreg[i] = *(const floatx4*)(Vh + (size_t)(jbase + row) * D + col);
+            }
+        }
+    };
+    if (n_tiles > 0) fetch_tile(0);
+
     for (int j = 0; j < n_tiles; ++j) {
         const int jbase = j * BC;
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < BC * D / 4 / 256; ++i) {
+        for (int i = 0; i < LD; ++i) {
             const int ch = tid + 256 * i;
             const int row = ch / (D / 4), col = (ch % (D / 4)) * 4;
-            floatx4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-            if (jbase + row < N) {
-                kv = *(const floatx4*)(Kh + (size_t)(jbase + row) * D + col);
-                vv = *(const floatx4*)(Vh + (size_t)(jbase + row) * D + col);
-            }
-            Ks[row * KLD + col] = kv[0];
-            Ks[row * KLD + col + 1] = kv[1];
-            Ks[row * KLD + col + 2] = kv[2];
-            Ks[row * KLD + col + 3] = kv[3];
-            *(floatx4*)(Vs + row * D + col) = vv;
+            Ks[row * KLD + col] = kreg[i][0];
+            Ks[row * KLD + col + 1] = kreg[i][1];
+            Ks[row * KLD + col + 2] = kreg[i][2];
+            Ks[row * KLD + col + 3] = kreg[i][3];
+            *(floatx4*)(Vs + row * D + col) = vreg[i];
         }
         __syncthreads();
+        if (j + 1 < n_tiles) fetch_tile(jbase + BC);
         if (CAUSAL && jbase > q0w + 31) continue;  // every key of this tile is masked for this wavefront
 
         // Logit: S^T[key, query]
@@ -102,7 +117,7 @@ __global__ __launch_bounds__(256) void fwd_f32_kernel(const float* __restrict__ 
         for (int r = 0; r < 16; ++r) {
             float x = __builtin_fmaf(s[r], c, -m_new);
             if (masked) x = (okmask >> r) & 1u ? x : -INFINITY;
-            p[r] = exp2f(x);
+            p[r] = __builtin_amdgcn_exp2f(x);
             lsum += p[r];
         }
         // Attend: O^T[dcol, query] += V^T[dcol, key] P^T[key, query]; step r contracts the two keys

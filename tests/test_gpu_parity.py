@@ -337,6 +337,20 @@ def test_blocksparse_lists_out_of_range_are_clamped_not_followed():
     assert out.shape == (1, 2, 700, 64)     # completed; values are unspecified for invalid lists
 
 
+@pytest.mark.parametrize("mask", [0, 1])
+def test_f32_large_problem_sampled_rows(mask):
+    """fp32 path on a problem big enough for its 128-rows-per-workgroup form (1024 row blocks); the small shapes
+    above run the form that splits the keys over the wavefronts of a workgroup."""
+    import torch
+    w = synth.custom("f32_large", 4, 8, 4096 + 40, 64, "f32", mask, seed=123 + mask)
+    q, k, v = synth.make_qkv(w)
+    out = run_entry("fused", w, q, k, v)
+    rows = sample_rows(w.N, 12, seed=9)
+    ref = oracle_rows(w, q, k, v, rows=rows)
+    check_close(to_host_f64(out[:, :, torch.from_numpy(rows).cuda(), :]), ref, "f32", w.name)
+    assert torch.isfinite(out).all()
+
+
 def test_status_codes_on_device_buffers():
     import torch
     import paper_2107_06419_amd as fa

@@ -15,7 +15,30 @@ import sqlite3
 import sys
 
 
+def demangle_simple(name: str) -> str:
+    """Names the profiler leaves mangled (its demangler gives up on some bf16 signatures): nested name plus
+    integer / bool template arguments is all that this library's kernels use."""
+    m = re.match(r"_ZN((?:\d+[A-Za-z_]\w*?)+?)(I(?:L[ibjm]n?\d+E)+E)?E", name)
+    if not m:
+        return name
+    parts, rest = [], m.group(1)
+    while rest:
+        n = int(re.match(r"\d+", rest).group(0))
+        k = len(str(n))
+        parts.append(rest[k:k + n])
+        rest = rest[k + n:]
+    out = "::".join(parts)
+    if m.group(2):
+        args = []
+        for kind, neg, val in re.findall(r"L([ibjm])(n?)(\d+)E", m.group(2)):
+            args.append(("true" if val == "1" else "false") if kind == "b" else ("-" if neg else "") + val)
+        out += "<" + ", ".join(args) + ">"
+    return out
+
+
 def short(name: str) -> str:
+    if name.startswith("_ZN"):
+        name = demangle_simple(name)
     name = re.sub(r"\(.*", "", name).replace("void ", "")
     return name[:72]
 

@@ -44,7 +44,7 @@ def main() -> int:
     ap.add_argument("--cpu-rows-per-head", type=int, default=16384, help="oracle sample size (0 = skip the cpu_baseline leg)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (heads shard with no exchange; see DESIGN.md); use --gpus 1",
+        print("bench.py: this build runs on one GPU only: the heads of a batch are independent, so more GPUs would each take a share of them with no exchange; use --gpus 1",
               file=sys.stderr)
         return 2
 

@@ -351,6 +351,41 @@ def test_f32_large_problem_sampled_rows(mask):
     assert torch.isfinite(out).all()
 
 
+def test_fused_entry_points_replay_from_a_hip_graph():
+    """The library only enqueues kernels on the caller's stream (no allocation, no host synchronisation, no
+    memset), so its calls can be captured.  Each replay is compared bit for bit with the eager result, with
+    eager work and synchronisations between the replays."""
+    import torch
+    import paper_2107_06419_amd as fa
+    w = synth.custom("graph", 2, 4, 1300, 64, "bf16", 1, seed=77)
+    q, k, v = synth.make_qkv(w)
+    dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+    kq = dq[:, :, :300, :].contiguous()
+    eager_self, eager_cross = torch.empty_like(dq), torch.empty_like(kq)
+    fa.flat_attn_fwd(dq, dk, dv, eager_self, w.scale, 1)
+    fa.flat_attn_fwd_cross(kq, dk, dv, eager_cross, w.scale, 1, None)
+    torch.cuda.synchronize()
+    out_self, out_cross = torch.zeros_like(dq), torch.zeros_like(kq)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            fa.flat_attn_fwd(dq, dk, dv, out_self, w.scale, 1, stream=side)
+            fa.flat_attn_fwd_cross(kq, dk, dv, out_cross, w.scale, 1, None, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        out_self.fill_(float("nan"))
+        out_cross.fill_(float("nan"))
+        scratch = (dq.float() * (rep + 1)).sum()   # unrelated eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_self.view(torch.int16), eager_self.view(torch.int16)), f"replay {rep}"
+        assert torch.equal(out_cross.view(torch.int16), eager_cross.view(torch.int16)), f"replay {rep}"
+        assert torch.isfinite(scratch)
+
+
 def test_status_codes_on_device_buffers():
     import torch
     import paper_2107_06419_amd as fa

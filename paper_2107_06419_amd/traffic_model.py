@@ -75,6 +75,16 @@ def intensity_fused(B: int, H: int, N: int, d: int) -> float:
     return (2 * B * N * N * D) / (4 * B * N * D)
 
 
+def logit_attend_share(N: int, D: int, ffn_multiple: int = 4) -> float:
+    """Share of one attention block's multiply-accumulates that sits in the Logit and Attend operators: N^2 D each,
+    against 4 N D^2 for the Q/K/V/O projections and 2 * ffn_multiple N D^2 for the two feed-forward layers
+    (operator list of section 2).  The paper reports the measured runtime share of the two operators growing
+    with the sequence length (section 7, block- and model-level discussion); the operation count reproduces it."""
+    la = 2 * N * N * D
+    rest = 4 * N * D * D + 2 * ffn_multiple * N * D * D
+    return la / (la + rest)
+
+
 # ----------------------------------------------------------------------------------------------------------
 # This library's fused kernel.
 

@@ -125,3 +125,13 @@ def test_measured_traffic_is_bracketed_by_the_model():
             tot, model = m["unfused_fetch"] + m["unfused_write"], r["unfused_model"]["fetch"] + r["unfused_model"]["write"]
             assert model <= tot * 1.02 and tot <= 1.35 * model
             assert tot > 50 * (m["fused_fetch"] + m["fused_write"])
+
+
+def test_logit_attend_share_follows_the_papers_runtime_shares():
+    """The paper gives measured runtime shares; operation counts should land within a few points of them (the
+    other operators run closer to peak than Logit/Attend do, so the measured share is the slightly larger one)."""
+    g = json.load(open(os.path.join(GOLDEN, "logit_attend_runtime_share.json")))
+    for N, pct in zip(g["sequence_lengths"], g["runtime_share_percent"]):
+        share = 100.0 * tm.logit_attend_share(N, 768)
+        assert pct - 3.0 <= share <= pct + 0.5, (N, share, pct)
+    assert tm.logit_attend_share(1, 768) < 1e-3 and tm.logit_attend_share(1 << 24, 768) > 0.999

@@ -403,9 +403,9 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
             shift(blk, masked, xc);
             softmax_b(xc, pc, bsum);
 #pragma unroll
-            for (int g = 0; g < kMfmaPerStep; ++g) {
+            for (int g = 0; g < kMfmaPerStep; ++g) {  // vector work first: measured about 1 % faster than MFMA first
+                __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);  // one MFMA's share of the vector work
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);             // one MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);  // its share of the vector work
             }
         } else {
             // two regions; the single V fragment set (vp and vc are the same registers) is refilled between them

@@ -200,6 +200,6 @@ const char* flat_attn_status_string(int status) {
     }
 }
 
-int flat_attn_version(void) { return 100; }
+int flat_attn_version(void) { return 200; }
 
 }  // extern "C"

@@ -386,6 +386,36 @@ def test_fused_entry_points_replay_from_a_hip_graph():
         assert torch.isfinite(scratch)
 
 
+def test_many_small_heads_every_entry_point():
+    """2000 heads of 33 positions: the grid is all heads, every tile is ragged."""
+    w = synth.custom("many_heads", 50, 40, 33, 64, "bf16", 1, seed=8)
+    q, k, v = synth.make_qkv(w)
+    ref = oracle_rows(w, q, k, v)
+    check_close(to_host_f64(run_entry("fused", w, q, k, v)), ref, "bf16", "fused many heads")
+    check_close(to_host_f64(run_entry("unfused", w, q, k, v)), ref, "bf16", "unfused many heads")
+    wf = synth.custom("many_heads_f32", 50, 40, 33, 64, "f32", 1, seed=8)
+    qf, kf, vf = synth.make_qkv(wf)
+    check_close(to_host_f64(run_entry("fused", wf, qf, kf, vf)), oracle_rows(wf, qf, kf, vf), "f32", "f32 many heads")
+
+
+def test_cross_with_more_queries_than_keys():
+    import torch
+    import paper_2107_06419_amd as fa
+    for d in (64, 128):
+        q = synth.tensor_f32((2, 2, 700, d), 61, 0, "normal", 1.0)
+        k = synth.tensor_f32((2, 2, 100, d), 61, 1, "normal", 1.0)
+        v = synth.tensor_f32((2, 2, 100, d), 61, 2, "normal", 1.0)
+        q, k, v = (synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(x)).reshape(x.shape) for x in (q, k, v))
+        dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+        out = torch.full_like(dq, float("nan"))
+        fa.flat_attn_fwd_cross(dq, dk, dv, out, 0.1, 0, None)
+        torch.cuda.synchronize()
+        check_close(to_host_f64(out), oracle.attention_cross(q, k, v, float(np.float32(0.1)), 0), "bf16", "cross Nq > Nk")
+        with pytest.raises(fa.FlatAttnError) as e:
+            fa.flat_attn_fwd_cross(dq, dk, dv, out, 0.1, 1, None)   # causal needs Nk >= Nq
+        assert e.value.status == -3
+
+
 def test_status_codes_on_device_buffers():
     import torch
     import paper_2107_06419_amd as fa

@@ -20,7 +20,6 @@ Kernel side
 from __future__ import annotations
 
 import json
-import math
 import os
 from dataclasses import dataclass
 

@@ -93,7 +93,8 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kernel_ms = sum(s.elapsed_time(e) for s, e in zip(starts, ends)) / args.steps
+    per_launch = sorted(s.elapsed_time(e) for s, e in zip(starts, ends))
+    kernel_ms = sum(per_launch) / args.steps
     flops = w.flops_useful
     tflops = flops / (ms_per_step * 1e-3) / 1e12
     kernel_tflops = flops / (kernel_ms * 1e-3) / 1e12
@@ -158,6 +159,7 @@ def main() -> int:
         cpu = {"value": round(cpu_flops / cpu_s / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.hw_threads(), "kind": "oracle",
                "sample": f"{rows.size} evenly spaced query rows of each of the {w.B * w.H} heads ({cpu_s:.2f} s, fp64)",
                "seconds": round(cpu_s, 3),
+               "seconds_all_rows_extrapolated": round(cpu_s * (w.flops_useful / cpu_flops), 1),
                "gpu_vs_oracle_max_abs": float(diff.max()), "gpu_vs_oracle_mean_rel": float(diff.sum() / np.abs(ref).sum())}
 
     peak = PEAK_BF16_TFLOPS if is_bf16 else PEAK_F32_TFLOPS
@@ -179,6 +181,7 @@ def main() -> int:
         "pct_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2) if is_bf16 else None,
         "roofline": {"bound": "mfma", "achieved": round(kernel_tflops, 2), "peak": peak, "unit": "TFLOP/s",
                      "frac": round(kernel_tflops / peak, 4), "kernel_ms": round(kernel_ms, 5),
+                     "kernel_ms_median": round(per_launch[len(per_launch) // 2], 5), "kernel_ms_min": round(per_launch[0], 5),
                      "traffic": None if traffic is None else traffic.get("fused_bytes_per_launch")},
         "hbm_bytes": {"fused_algorithmic": fused_alg_bytes, "unfused_algorithmic": unfused_alg_bytes,
                       "fused_measured": None if traffic is None else traffic.get("fused_bytes_per_launch"),

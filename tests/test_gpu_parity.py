@@ -416,6 +416,55 @@ def test_cross_with_more_queries_than_keys():
         assert e.value.status == -3
 
 
+def test_randomized_small_problems_all_bf16_entry_points():
+    """Seeded random shapes (lengths 1..900, both head sizes, both masks, random key counts and block patterns)
+    through the self-attention, cross-length, block-sparse and unfused entry points, each against the oracle."""
+    import random
+    import torch
+    import paper_2107_06419_amd as fa
+    rng = random.Random(20210706)
+
+    def rounded(shape, seed, tid, mult=1.0):
+        x = synth.tensor_f32(shape, seed, tid, "normal", mult)
+        return synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(x)).reshape(shape)
+
+    for case in range(36):
+        B, H, d, mask = rng.randint(1, 3), rng.randint(1, 3), rng.choice([64, 128]), rng.randint(0, 1)
+        Nk = rng.choice([1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 511, 512, 513, 640, 900])
+        Nq = rng.choice([1, 17, 64, 100, 256, 257, Nk]) if rng.random() < 0.5 else Nk
+        if mask == 1 and Nq > Nk:
+            Nq = Nk
+        scale = float(np.float32(rng.choice([0.05, 0.125, 0.3])))
+        mult = rng.choice([1.0, 2.0])
+        seed = 9000 + case
+        q = rounded((B, H, Nq, d), seed, 0, mult)
+        k = rounded((B, H, Nk, d), seed, 1, mult)
+        v = rounded((B, H, Nk, d), seed, 2)
+        lens = [rng.randint(1, Nk) for _ in range(B)] if rng.random() < 0.5 else None
+        print(f"case {case}: B={B} H={H} Nq={Nq} Nk={Nk} d={d} mask={mask} scale={scale} mult={mult} lens={lens}", flush=True)
+        dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+        out = torch.full_like(dq, float("nan"))
+        kv = None if lens is None else torch.tensor(lens, dtype=torch.int32, device="cuda")
+        fa.flat_attn_fwd_cross(dq, dk, dv, out, scale, mask, kv)
+        torch.cuda.synchronize()
+        ref = oracle.attention_cross(q, k, v, scale, mask, kv_lens=None if lens is None else np.array(lens))
+        check_close(to_host_f64(out), ref, "bf16", f"random cross {case}")
+        if Nq == Nk and lens is None:
+            w = synth.custom("rand", B, H, Nk, d, "bf16", mask, scale=scale, seed=seed)
+            out2 = torch.full_like(dq, float("nan"))
+            fa.flat_attn_fwd(dq, dk, dv, out2, scale, mask)
+            ws = torch.empty(fa.flat_attn_unfused_workspace_bytes(B, H, Nk, d) // 4, dtype=torch.float32, device="cuda")
+            out3 = torch.full_like(dq, float("nan"))
+            fa.flat_attn_unfused(dq, dk, dv, out3, scale, mask, ws)
+            torch.cuda.synchronize()
+            assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+            check_close(to_host_f64(out3), ref, "bf16", f"random unfused {case}")
+            if mask == 0:
+                offs, ids = synth.random_block_pattern(B * H * -(-Nk // 256), -(-Nk // 64), rng.choice([0.3, 0.6, 1.0]), seed=seed)
+                got = _run_blocksparse(w, q, k, v, offs, ids)
+                check_close(to_host_f64(got), oracle.attention_blocksparse(q, k, v, scale, offs, ids), "bf16", f"random sparse {case}")
+
+
 def test_status_codes_on_device_buffers():
     import torch
     import paper_2107_06419_amd as fa

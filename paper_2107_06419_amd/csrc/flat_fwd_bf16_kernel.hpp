@@ -73,11 +73,13 @@ __device__ __forceinline__ void wait_vm() {
     __builtin_amdgcn_s_waitcnt((CNT & 15) | ((CNT >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
+constexpr int kMaxSparseTiles = 2048;  // block-sparse: listed tiles per row block that fit the LDS copy of the list (8 KiB)
+
+// Template parameters: D head dimension, QB 32-row blocks per wavefront, NW wavefronts per workgroup, STAGES
+// depth of the K/V ring, CAUSAL mask, SPARSE block-sparse variant (the workgroup visits only the 64-key tiles
+// listed for its row block, ids ascending, staged in LDS behind the ring; everything else as in the dense kernel).
 // Two wavefronts per SIMD (256 registers each), except 64 rows per wavefront at d = 128, whose accumulators alone
 // need more: that shape runs one wavefront per SIMD with the full 512 registers.
-// SPARSE: block-sparse variant.  The workgroup visits only the 64-key tiles listed for its row block (ids in
-// ascending order, staged in LDS behind the ring); everything else is as in the dense kernel.
-constexpr int kMaxSparseTiles = 2048;  // listed tiles per row block that fit the LDS list (8 KiB)
 
 template <int D, int QB, int NW, int STAGES, bool CAUSAL, bool SPARSE = false>
 __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf16_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,

@@ -7,7 +7,11 @@ A step is one call of flat_attn_fwd (the whole fused Logit-softmax-Attend path) 
 batch of the named workload, inputs resident in HBM.  Prints ONE JSON line: whole-job throughput
 in TFLOP/s (4*B*H*N^2*d flops per step; for a causal workload the useful 2*B*H*N*(N+1)*d), the
 MFMA roofline of the fused kernel measured with HIP events inside the timed region, the unfused
-baseline's time and HBM bytes for comparison, and the CPU oracle timed on a bounded sample.
+baseline's time and HBM bytes for comparison, the instruction-mix ceiling probes, the other four
+workloads in compact form, and the CPU oracle timed on a bounded sample.
+
+Exit status: 0 = measured and within tolerance; 2 = more than one GPU asked for; 3 = no GPU;
+4 = some output compared with the oracle broke the stated tolerance (the JSON line is still printed).
 """
 import argparse
 import json
@@ -21,7 +25,25 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA peak
 PEAK_F32_TFLOPS = 157.3    # published fp32 matrix/vector peak (the fp32 variant runs on fp32 MFMA)
+PEAK_HBM_GBPS = 8000.0     # published HBM3E bandwidth
 METRIC = "fused attention TFLOP/s and % bf16 MFMA peak at N=16K,d=64; HBM bytes vs unfused"
+# tolerances of the build: (max |dO|, sum|dO| / sum|O_ref|) over all compared elements, plus a bound on
+# sum|dO| / sum|O_ref| taken row by row, so that one wrong row or tile cannot hide in the aggregate
+TOL = {"bf16": (2e-2, 5e-3, 3e-2), "f32": (1e-4, 1e-4, 1e-3)}
+ROW_FLOOR = {"bf16": 1e-4, "f32": 1e-6}  # absolute slack per element of a row, for rows whose reference is all but zero
+PREWARM_MS = 50.0          # GPU time spent on the fused kernel before anything is timed: clocks settle in about 25 ms
+
+
+def compare(got, ref, dtype):
+    """Errors of `got` [..., rows, d] against the oracle's `ref`, and whether they are within tolerance."""
+    import numpy as np
+    diff = np.abs(got - ref)
+    max_abs = float(diff.max())
+    mean_rel = float(diff.sum() / max(np.abs(ref).sum(), 1e-300))
+    row_rel = float((np.maximum(diff.sum(axis=-1) - got.shape[-1] * ROW_FLOOR[dtype], 0.0) / np.maximum(np.abs(ref).sum(axis=-1), 1e-300)).max())
+    t = TOL[dtype]
+    ok = bool(np.isfinite(got).all() and max_abs <= t[0] and mean_rel <= t[1] and row_rel <= t[2])
+    return {"max_abs": max_abs, "mean_rel": mean_rel, "worst_row_rel": row_rel, "ok": ok}
 
 
 def load_traffic(workload: str):
@@ -42,6 +64,9 @@ def main() -> int:
     ap.add_argument("--unfused-steps", type=int, default=3, help="timed launches of the unfused baseline (0 = skip)")
     ap.add_argument("--mfma-probe-launches", type=int, default=24, help="launches of the MFMA-only probe per operand kind (0 = skip)")
     ap.add_argument("--cpu-rows-per-head", type=int, default=16384, help="oracle sample size (0 = skip the cpu_baseline leg)")
+    ap.add_argument("--mix-probe-launches", type=int, default=12, help="launches of each instruction-mix probe level (0 = skip)")
+    ap.add_argument("--others", type=int, default=1, help="1 = also time and check the other four workloads, compactly (0 = skip)")
+    ap.add_argument("--other-rows-per-head", type=int, default=256, help="oracle sample per head for the other workloads")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only: the heads of a batch are independent, so more GPUs would each take a share of them with no exchange; use --gpus 1",
@@ -79,6 +104,20 @@ def main() -> int:
     def step():
         fwd(dq, dk, dv, out, w.scale, w.mask, stream)
 
+    def prewarm(fn, ms=PREWARM_MS):
+        """Launch fn until `ms` of GPU time have passed (HIP events); returns the GPU milliseconds spent."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        spent = 0.0
+        while spent < ms:
+            e0.record(stream)
+            for _ in range(8):
+                fn()
+            e1.record(stream)
+            e1.synchronize()
+            spent += e0.elapsed_time(e1)
+        return spent
+
+    clock_prewarm_ms = prewarm(step)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -141,6 +180,40 @@ def main() -> int:
             probe[name] = round(fa.flat_attn_mfma_probe_flops(iters) / (ms * 1e-3) / 1e12, 1)
         probe["fused_vs_random_operand_mfma"] = round(kernel_tflops / probe["random_operands_tflops"], 4)
 
+    # the fused step's instruction mix on synthetic data: registers only, then with the kernel's data movement
+    # added rung by rung (level 3 has the structure of the fused kernel's main loop)
+    mix = None
+    if args.mix_probe_launches > 0 and is_bf16:
+        sink = torch.empty(fa.flat_attn_mix_probe_sink_bytes() // 4, dtype=torch.float32, device="cuda")
+        src = torch.randn(fa.flat_attn_mix_probe_src_bytes() // 2, device="cuda").to(torch.bfloat16)
+        iters = 500
+        mix = {}
+        names = ("registers_only_tflops", "plus_lds_operand_reads_tflops", "plus_tile_barrier_tflops", "plus_global_to_lds_streaming_tflops")
+        for level, name in enumerate(names):
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.mix_probe_launches + 1)]
+            evs[0].record(stream)
+            for i in range(args.mix_probe_launches):
+                fa.flat_attn_mix_probe(sink, src, level, iters, stream)
+                evs[i + 1].record(stream)
+            torch.cuda.synchronize()
+            tail = max(1, args.mix_probe_launches // 2)
+            ms = evs[-tail - 1].elapsed_time(evs[-1]) / tail
+            mix[name] = round(fa.flat_attn_mix_probe_flops(iters) / (ms * 1e-3) / 1e12, 1)
+        prewarm(step, 10.0)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(20):
+            step()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        again = flops / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e12  # the fused kernel right after the probes: same clocks
+        mix["fused_kernel_tflops_same_minute"] = round(again, 1)
+        mix["fused_vs_registers_only"] = round(again / mix[names[0]], 4)
+        mix["fused_vs_full_structure"] = round(again / mix[names[3]], 4)
+        mix["registers_only_frac_of_peak"] = round(mix[names[0]] / PEAK_BF16_TFLOPS, 4)
+        del sink, src
+
+    parity_ok = True
     cpu = None
     if args.cpu_rows_per_head > 0:
         import oracle
@@ -154,13 +227,68 @@ def main() -> int:
             cpu_flops = 4.0 * w.B * w.H * w.d * float(np.sum(rows + 1))
         else:
             cpu_flops = 4.0 * w.B * w.H * rows.size * w.N * w.d
+        step()
+        torch.cuda.synchronize()
         got = out[:, :, torch.from_numpy(rows).cuda(), :].float().cpu().numpy().astype(np.float64)
-        diff = np.abs(got - ref)
+        cmp_ = compare(got, ref, w.dtype)
+        parity_ok = parity_ok and cmp_["ok"]
         cpu = {"value": round(cpu_flops / cpu_s / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.hw_threads(), "kind": "oracle",
                "sample": f"{rows.size} evenly spaced query rows of each of the {w.B * w.H} heads ({cpu_s:.2f} s, fp64)",
                "seconds": round(cpu_s, 3),
                "seconds_all_rows_extrapolated": round(cpu_s * (w.flops_useful / cpu_flops), 1),
-               "gpu_vs_oracle_max_abs": float(diff.max()), "gpu_vs_oracle_mean_rel": float(diff.sum() / np.abs(ref).sum())}
+               "gpu_vs_oracle_max_abs": cmp_["max_abs"], "gpu_vs_oracle_mean_rel": cmp_["mean_rel"],
+               "gpu_vs_oracle_worst_row_rel": cmp_["worst_row_rel"], "within_tolerance": cmp_["ok"],
+               "tolerance": {"max_abs": TOL[w.dtype][0], "mean_rel": TOL[w.dtype][1], "worst_row_rel": TOL[w.dtype][2]}}
+
+    # the other workloads of the benchmark set, compactly: time of the fused kernel and a sampled oracle check
+    others = None
+    if args.others:
+        import oracle
+        others = []
+        del dq, dk, dv, out
+        for name, ow in synth.WORKLOADS.items():
+            if name == w.name:
+                continue
+            obf = ow.dtype == "bf16"
+            oq, ok_, ov = synth.make_qkv(ow)
+
+            def odev(x):
+                if not obf:
+                    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+                return torch.from_numpy(synth.f32_to_bf16_bits(x).reshape(x.shape).view(np.int16)).cuda().view(torch.bfloat16)
+
+            tq, tk, tv = odev(oq), odev(ok_), odev(ov)
+            to = torch.empty_like(tq)
+            ofwd = fa.flat_attn_fwd if obf else fa.flat_attn_fwd_f32
+
+            def ostep():
+                ofwd(tq, tk, tv, to, ow.scale, ow.mask, stream)
+
+            prewarm(ostep, 30.0)
+            n = 30
+            es = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+            for a, b in es:
+                a.record(stream)
+                ostep()
+                b.record(stream)
+            torch.cuda.synchronize()
+            ts = sorted(a.elapsed_time(b) for a, b in es)
+            med = ts[n // 2]
+            nrows = min(args.other_rows_per_head, ow.N)
+            rows = np.unique(np.concatenate([np.arange(0, ow.N, max(1, ow.N // nrows), dtype=np.int64)[:nrows],
+                                             np.array([0, ow.N - 1], dtype=np.int64)]))
+            ref = oracle.attention(oq.astype(np.float64), ok_.astype(np.float64), ov.astype(np.float64), ow.scale, ow.mask, rows=rows)
+            got = to[:, :, torch.from_numpy(rows).cuda(), :].float().cpu().numpy().astype(np.float64)
+            c_ = compare(got, ref, ow.dtype)
+            parity_ok = parity_ok and c_["ok"]
+            opeak = PEAK_BF16_TFLOPS if obf else PEAK_F32_TFLOPS
+            otf = ow.flops_useful / (med * 1e-3) / 1e12
+            others.append({"workload": name, "dtype": ow.dtype, "mask": "causal" if ow.mask else "none",
+                           "ms_median": round(med, 5), "ms_min": round(ts[0], 5), "tflops_useful": round(otf, 2),
+                           "frac_of_peak": round(otf / opeak, 4), "rows_checked_per_head": int(rows.size),
+                           "max_abs": c_["max_abs"], "mean_rel": c_["mean_rel"], "worst_row_rel": c_["worst_row_rel"],
+                           "within_tolerance": c_["ok"]})
+            del tq, tk, tv, to, oq, ok_, ov
 
     peak = PEAK_BF16_TFLOPS if is_bf16 else PEAK_F32_TFLOPS
     rec = {
@@ -170,6 +298,7 @@ def main() -> int:
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "clock_prewarm_ms": round(clock_prewarm_ms, 1),
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True,
         "scaling": "weak",
@@ -188,9 +317,15 @@ def main() -> int:
                       "unfused_measured": None if traffic is None else traffic.get("unfused_bytes_per_launch")},
         "unfused": unfused,
         "mfma_probe": probe,
+        "mix_ceiling": mix,
         "cpu_baseline": cpu,
+        "other_workloads": others,
+        "parity_ok": parity_ok,
     }
     print(json.dumps(rec))
+    if not parity_ok:
+        print("bench.py: an output compared with the oracle is outside the stated tolerance", file=sys.stderr)
+        return 4
     return 0
 
 

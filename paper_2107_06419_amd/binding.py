@@ -79,6 +79,14 @@ def load_library():
     lib.flat_attn_mfma_probe_flops.argtypes = [i]
     lib.flat_attn_mfma_probe.restype = i
     lib.flat_attn_mfma_probe.argtypes = [vp, sz, i, i, vp]
+    lib.flat_attn_mix_probe_sink_bytes.restype = sz
+    lib.flat_attn_mix_probe_sink_bytes.argtypes = []
+    lib.flat_attn_mix_probe_src_bytes.restype = sz
+    lib.flat_attn_mix_probe_src_bytes.argtypes = []
+    lib.flat_attn_mix_probe_flops.restype = ctypes.c_double
+    lib.flat_attn_mix_probe_flops.argtypes = [i]
+    lib.flat_attn_mix_probe.restype = i
+    lib.flat_attn_mix_probe.argtypes = [vp, sz, vp, sz, i, i, vp]
     lib.flat_attn_status_string.restype = ctypes.c_char_p
     lib.flat_attn_status_string.argtypes = [i]
     lib.flat_attn_version.restype = i
@@ -230,3 +238,24 @@ def flat_attn_mfma_probe(sink, iters: int, random_operands: bool, stream=None) -
         raise ValueError("sink must be a contiguous GPU tensor")
     _check(load_library().flat_attn_mfma_probe(sink.data_ptr(), sink.numel() * sink.element_size(), int(iters),
                                                1 if random_operands else 0, _stream_handle(stream)))
+
+
+def flat_attn_mix_probe_sink_bytes() -> int:
+    return int(load_library().flat_attn_mix_probe_sink_bytes())
+
+
+def flat_attn_mix_probe_src_bytes() -> int:
+    return int(load_library().flat_attn_mix_probe_src_bytes())
+
+
+def flat_attn_mix_probe_flops(iters: int) -> float:
+    return float(load_library().flat_attn_mix_probe_flops(int(iters)))
+
+
+def flat_attn_mix_probe(sink, src, level: int, iters: int, stream=None) -> None:
+    """Instruction-mix probe of the fused kernel's step; `sink` / `src` are device tensors of at least
+    flat_attn_mix_probe_sink_bytes() / flat_attn_mix_probe_src_bytes() bytes."""
+    if not sink.is_cuda or not sink.is_contiguous() or not src.is_cuda or not src.is_contiguous():
+        raise ValueError("sink and src must be contiguous GPU tensors")
+    _check(load_library().flat_attn_mix_probe(sink.data_ptr(), sink.numel() * sink.element_size(), src.data_ptr(),
+                                              src.numel() * src.element_size(), int(level), int(iters), _stream_handle(stream)))

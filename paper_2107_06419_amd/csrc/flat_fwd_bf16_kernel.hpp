@@ -60,7 +60,9 @@ struct Bf16Cfg {
 // One wave-wide global -> LDS copy, 16 bytes per lane: lane l's bytes land at lds_base + 16 l.
 // Issued as inline asm so that the compiler does not serialise later LDS reads of OTHER stages
 // behind it; completion is awaited explicitly with wait_vm<n>() before the stage is published by
-// a barrier.  lds_base must be wave-uniform.
+// a barrier.  lds_base must be wave-uniform.  The statement overwrites m0, which the compiler reserves and does
+// not accept on a clobber list; the kernels here contain nothing else that lives in m0 (no indirect register
+// indexing, no LDS-direct or message instructions), and a host-side test checks the generated assembly for that.
 __device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(gbase) : "memory");
 }
@@ -527,7 +529,8 @@ inline hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* 
     const int blocks_per_xcd = (n_blocks + 7) / 8;
     auto kern = fwd_bf16_kernel<D, QB, NW, STAGES, CAUSAL, SPARSE>;
     constexpr int lds = Bf16Cfg<D, STAGES, NW>::LDS_BYTES + (SPARSE ? kMaxSparseTiles * (int)sizeof(int) : 0);
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    static std::atomic<uint64_t> attr_done{0};  // one flag per kernel instantiation
+    hipError_t e = allow_dynamic_lds((const void*)kern, lds, &attr_done);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(blocks_per_xcd * 8), dim3(64 * NW), lds, stream, (const bf16*)Q, (const bf16*)K,
                        (const bf16*)V, (bf16*)O, prob, n_qtiles, n_blocks, blocks_per_xcd, scale * kLog2e);

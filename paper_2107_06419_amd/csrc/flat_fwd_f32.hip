@@ -214,8 +214,13 @@ __global__ __launch_bounds__(256) void fwd_f32_splitkeys_kernel(const float* __r
             Ks[row * KLD + col + 3] = kv[3];
             *(floatx4*)(Vs + row * D + col) = vv;
         }
-        // the region is private to this wavefront: its own LDS writes are ordered before its reads
+        // The region is private to this wavefront, but lanes read what other lanes wrote: order the wavefront's
+        // LDS stores before its reads, and the reads before the next tile's stores.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
         f32_tile<D, CAUSAL>(Ks, Vs, jbase, N, q0w, qrow, c, qf, oacc, m, lsum, l32, half);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
 
     // merge: wavefronts 1..3 publish (m, l, O) in their own regions (layout [value][lane], conflict-free)
@@ -278,7 +283,8 @@ static hipError_t launch_cfg(const float* Q, const float* K, const float* V, flo
         const int blocks_per_xcd = (n_blocks + 7) / 8;
         constexpr int lds = 4 * (32 * (D + 1) + 32 * D) * (int)sizeof(float);
         auto kern = fwd_f32_splitkeys_kernel<D, CAUSAL>;
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        static std::atomic<uint64_t> attr_done{0};
+        hipError_t e = allow_dynamic_lds((const void*)kern, lds, &attr_done);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3(blocks_per_xcd * 8), dim3(256), lds, stream, Q, K, V, O, N, n_qtiles, n_blocks,
                            blocks_per_xcd, scale * kLog2e);

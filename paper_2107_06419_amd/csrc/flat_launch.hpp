@@ -3,8 +3,24 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stddef.h>
+#include <stdint.h>
+
+#include <atomic>
 
 namespace flat {
+
+// Raise a kernel's dynamic-LDS limit once per device (bit = device ordinal) instead of on every launch.
+inline hipError_t allow_dynamic_lds(const void* kern, int lds_bytes, std::atomic<uint64_t>* done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done->load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e == hipSuccess) done->fetch_or(bit, std::memory_order_release);
+    return e;
+}
+
 
 // Sequence geometry of one fused bf16 launch.  Self-attention is Nq = Nk, causal_offset = 0, kv_lens = null.
 struct Bf16Problem {
@@ -60,5 +76,14 @@ hipError_t launch_unfused_bf16(const void* Q, const void* K, const void* V, void
 hipError_t launch_mfma_probe(float* sink, int iters, int random_operands, hipStream_t stream);
 double mfma_probe_flops(int iters);
 size_t mfma_probe_sink_bytes();
+
+// Instruction-mix probe (flat_probe.hip): 512 workgroups x 4 wavefronts loop over the fused d = 64 kernel's step
+// (16 MFMAs + the softmax of two 32-row blocks) on synthetic data.  level 0 = registers only, 1 = + LDS operand reads,
+// 2 = + one barrier per tile, 3 = + global -> LDS streaming of the tiles.  All operands are taken from `src`
+// (mix_probe_src_bytes() of any finite bf16 data).  One trip of `iters` is 8 steps.
+hipError_t launch_mix_probe(float* sink, const void* src, int level, int iters, hipStream_t stream);
+double mix_probe_flops(int iters);
+size_t mix_probe_sink_bytes();
+size_t mix_probe_src_bytes();
 
 }  // namespace flat

@@ -142,3 +142,51 @@ def test_blocksparse_entry_point_validation():
     assert sp(d=96) == -3 and sp(scale=-1.0) == -3
     assert sp(offs=0x9002) == -4 and sp(ids=0xA001) == -4 and sp(V=far[2] + 8) == -4
     assert sp(O=far[0]) == -7 and sp(offs=far[3] + 64) == -7 and sp(ids=far[3] + 128) == -7
+
+
+def test_mix_probe_validation():
+    lib = fa.load_library()
+    need_sink, need_src = fa.flat_attn_mix_probe_sink_bytes(), fa.flat_attn_mix_probe_src_bytes()
+    assert need_sink == 512 * 256 * 4 and need_src == 2 * 64 * 8192
+    assert fa.flat_attn_mix_probe_flops(1) == 512 * 4 * 8 * 16 * 32768.0 and fa.flat_attn_mix_probe_flops(0) == 0.0
+    sink, src = 0x1000000, 0x8000000
+
+    def probe(sink=sink, sink_bytes=need_sink, src=src, src_bytes=need_src, level=3, iters=4):
+        return lib.flat_attn_mix_probe(sink, sink_bytes, src, src_bytes, level, iters, None)
+
+    assert probe(sink=None) == -1 and probe(src=None) == -1
+    assert probe(level=4) == -3 and probe(level=-1) == -3
+    assert probe(iters=0) == -2 and probe(iters=(1 << 20) + 1) == -2
+    assert probe(sink=sink + 4) == -4 and probe(src=src + 2) == -4
+    assert probe(sink_bytes=need_sink - 1) == -5 and probe(src_bytes=need_src - 1) == -5
+    assert probe(src=sink + 16) == -7
+
+
+def test_streaming_asm_is_the_only_user_of_m0():
+    """The global -> LDS loads are inline assembly that overwrites m0 without being able to declare it.  Compile the
+    fused kernels to assembly and check that nothing else in them reads or writes m0."""
+    import shutil
+    import subprocess
+    import tempfile
+    from paper_2107_06419_amd import build as fb
+    hipcc = fb._hipcc()
+    if shutil.which(hipcc) is None and not os.path.exists(hipcc):
+        pytest.skip("hipcc not available")
+    src = os.path.join(ROOT, "paper_2107_06419_amd", "csrc", "flat_fwd_bf16.hip")
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "k.s")
+        subprocess.run([hipcc, *fb.FLAGS, "-S", "--cuda-device-only", "-o", out, src], check=True, capture_output=True)
+        inside, uses, dmas = False, [], 0
+        for line in open(out):
+            t = line.strip()
+            if t.startswith(";;#ASMSTART"):
+                inside = True
+            elif t.startswith(";;#ASMEND"):
+                inside = False
+            elif re.search(r"\bm0\b", t.split(";")[0]):
+                if inside:
+                    dmas += "s_mov_b32 m0" in t
+                else:
+                    uses.append(t)
+    assert dmas > 0, "no streaming load found: the check looks at the wrong file"
+    assert not uses, f"m0 is used outside the streaming asm: {uses[:5]}"

@@ -119,6 +119,30 @@ def test_full_size_workload_sampled_rows(name):
     assert bool((o32 <= vmax + 1e-2).all()) and bool((o32 >= vmin - 1e-2).all())
 
 
+def test_largest_workload_every_row():
+    """The 64K-key workload compared with the oracle on EVERY query row of every head (the sampled test above
+    looks at a few dozen rows per head).  The oracle takes the rows in slices and reports after each, so a
+    slow host shows progress instead of silence."""
+    import sys
+    import torch
+    w = synth.WORKLOADS["cfg4_extreme_64k"]
+    q, k, v = synth.make_qkv(w)
+    out = run_entry("fused", w, q, k, v)
+    q64, k64, v64 = (x.astype(np.float64) for x in (q, k, v))
+    worst_abs, num, den = 0.0, 0.0, 0.0
+    step = 4096
+    for r0 in range(0, w.N, step):
+        rows = np.arange(r0, min(r0 + step, w.N), dtype=np.int64)
+        ref = oracle.attention(q64, k64, v64, w.scale, w.mask, rows=rows)
+        got = to_host_f64(out[:, :, r0:r0 + rows.size, :])
+        check_close(got, ref, "bf16", f"{w.name} rows {r0}..{r0 + rows.size - 1}")  # aggregate of the slice + every row of it
+        diff = np.abs(got - ref)
+        worst_abs, num, den = max(worst_abs, float(diff.max())), num + float(diff.sum()), den + float(np.abs(ref).sum())
+        print(f"{w.name}: rows up to {r0 + rows.size} agree", file=sys.__stderr__, flush=True)
+    print(f"{w.name} all rows: max|dO| {worst_abs:.3e}, mean rel {num / den:.3e}", flush=True)
+    assert num / den <= 5e-3
+
+
 @pytest.mark.parametrize("name", ["cfg2_long_16k", "cfg3_wide_causal_8k"])
 def test_constant_value_columns_full_size(name):
     """V constant along keys => O equals that constant for any Q, K: checks that the row sum and the

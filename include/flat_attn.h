@@ -18,7 +18,10 @@
  *   - Q, K, V, O are DEVICE pointers to contiguous [B,H,N,d] arrays, d fastest; element type
  *     bf16 (flat_attn_fwd, flat_attn_unfused) or float (flat_attn_fwd_f32).  All four must
  *     be 16-byte aligned.  Q, K, V are only read.  O must not overlap Q, K or V.
- *   - Self-attention: queries and keys both number N.  Any N >= 1 is accepted.  d is 64 or 128.
+ *   - Self-attention: queries and keys both number N.  Any N >= 1 is accepted.
+ *   - Head dimension d: 32, 64, 96, 128 or 256 for the fused bf16 entry points (flat_attn_fwd, _fwd_cross,
+ *     _fwd_blocksparse, _fwd_tile): the head sizes of the model families in the paper's workload list (section 6,
+ *     "Workloads").  64 or 128 for flat_attn_fwd_f32 and flat_attn_unfused.  Anything else: FLAT_ERR_UNSUPPORTED.
  *   - scale multiplies the logits before softmax; it must be finite and >= 0.
  *   - mask_kind: FLAT_MASK_NONE, or FLAT_MASK_CAUSAL (key j contributes to query i iff j <= i;
  *     a masked key has probability exactly 0).
@@ -45,7 +48,7 @@ typedef enum {
     FLAT_OK = 0,
     FLAT_ERR_NULL = -1,        /* a required pointer is NULL */
     FLAT_ERR_SHAPE = -2,       /* B, H or N is not positive, or B*H*N*N / B*H*N*d overflows */
-    FLAT_ERR_UNSUPPORTED = -3, /* d not in {64,128}, unknown mask_kind or dtype, scale negative or not finite, causal with Nk < Nq */
+    FLAT_ERR_UNSUPPORTED = -3, /* head dimension not built, unknown mask_kind or dtype, scale negative or not finite, causal with Nk < Nq */
     FLAT_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
     FLAT_ERR_WORKSPACE = -5,   /* workspace_bytes is smaller than flat_attn_unfused_workspace_bytes() */
     FLAT_ERR_HIP = -6,         /* the HIP runtime refused a launch */
@@ -86,7 +89,7 @@ int flat_attn_fwd_cross(const void* Q, const void* K, const void* V, void* O,
 /*
  * Block-sparse variant.  The paper asks (section 8.2, compatibility with sparse-attention accelerators) whether
  * the Logit/Attend pair stays worth fusing when the N x N matrix is pruned, and prunes it randomly at 50 %.  On
- * this hardware pruning pays only at the granularity the kernel works at, so the pattern is given in blocks of
+ * this hardware pruning pays only at about the granularity the kernel works at, so the pattern is given in blocks of
  * FLAT_SPARSE_BLOCK_ROWS query rows x FLAT_SPARSE_BLOCK_KEYS keys: query i sees key j iff tile j / 64 is listed
  * for row block i / 256 of its (batch, head).  Unlisted tiles are neither loaded nor computed.
  *   Q, K, V, O: as flat_attn_fwd (self-attention, N <= 131072).  No causal form.
@@ -131,7 +134,7 @@ int flat_attn_unfused(const void* Q, const void* K, const void* V, void* O,
  * tile re-fetch the keys more often and fill the compute array less; more rows need more on-chip memory).
  * Here the exploration is done by measurement: the library is built with several shapes per head dimension,
  * flat_attn_fwd uses index 0, and flat_attn_fwd_tile runs any of them so that the choice can be re-timed.
- *   flat_attn_tile_shape_count(d): number of shapes for head dimension d (0 if d is not 64 or 128).
+ *   flat_attn_tile_shape_count(d): number of shapes for head dimension d (0 if d is not one of 32, 64, 96, 128, 256).
  *   flat_attn_tile_shape_get: fills *out (HOST pointer) for 0 <= index < count; FLAT_ERR_SHAPE otherwise.
  *   flat_attn_tile_shape_occupancy: workgroups of that shape resident per compute unit on the current
  *     device (registers and LDS permitting), or a negative flat_status; the only one of the three that

@@ -17,12 +17,17 @@ bool overlaps(const void* a, size_t abytes, const void* b, size_t bbytes) {
     return a0 < b0 + bbytes && b0 < a0 + abytes;
 }
 
-// Shape / pointer checks shared by all entry points.  `elem` = bytes per tensor element.
+// Head dimensions: the fused bf16 kernel is built for five, the fp32 variant and the unfused baseline for two.
+bool fused_bf16_head_dim(int d) { return d == 32 || d == 64 || d == 96 || d == 128 || d == 256; }
+bool basic_head_dim(int d) { return d == 64 || d == 128; }
+
+// Shape / pointer checks shared by all entry points.  `elem` = bytes per tensor element; `all_dims`: the entry
+// point takes every head dimension of the fused bf16 kernel.
 int check_common(const void* Q, const void* K, const void* V, const void* O, int B, int H, int N, int d, float scale,
-                 int mask_kind, size_t elem) {
+                 int mask_kind, size_t elem, bool all_dims = false) {
     if (!Q || !K || !V || !O) return FLAT_ERR_NULL;
     if (B <= 0 || H <= 0 || N <= 0) return FLAT_ERR_SHAPE;
-    if (d != 64 && d != 128) return FLAT_ERR_UNSUPPORTED;
+    if (!(all_dims ? fused_bf16_head_dim(d) : basic_head_dim(d))) return FLAT_ERR_UNSUPPORTED;
     if (mask_kind != FLAT_MASK_NONE && mask_kind != FLAT_MASK_CAUSAL) return FLAT_ERR_UNSUPPORTED;
     if (!(scale >= 0.0f) || isinf(scale)) return FLAT_ERR_UNSUPPORTED;  // also rejects NaN
     // B*H must fit the grid; B*H*N*d*elem and B*H*N*N*4 must fit 63 bits
@@ -44,7 +49,7 @@ extern "C" {
 
 int flat_attn_fwd(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
                   int mask_kind, void* stream) {
-    const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 2);
+    const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 2, true);
     if (rc != FLAT_OK) return rc;
     if ((unsigned long long)N * (unsigned)d * 2u > 0xffffffffULL) return FLAT_ERR_SHAPE;  // the kernel addresses one head with 32-bit byte offsets
     const flat::Bf16Problem prob{N, N, 0, H, nullptr, nullptr, nullptr, 0};
@@ -58,7 +63,7 @@ int flat_attn_fwd_cross(const void* Q, const void* K, const void* V, void* O, in
     // the checks of check_common, with separate lengths for the query side (Q, O) and the key side (K, V)
     if (!Q || !K || !V || !O) return FLAT_ERR_NULL;
     if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0) return FLAT_ERR_SHAPE;
-    if (d != 64 && d != 128) return FLAT_ERR_UNSUPPORTED;
+    if (!fused_bf16_head_dim(d)) return FLAT_ERR_UNSUPPORTED;
     if (mask_kind != FLAT_MASK_NONE && mask_kind != FLAT_MASK_CAUSAL) return FLAT_ERR_UNSUPPORTED;
     if (!(scale >= 0.0f) || isinf(scale)) return FLAT_ERR_UNSUPPORTED;
     if (mask_kind == FLAT_MASK_CAUSAL && Nk < Nq) return FLAT_ERR_UNSUPPORTED;  // some query would see no key
@@ -119,7 +124,7 @@ int flat_attn_unfused(const void* Q, const void* K, const void* V, void* O, int 
 
 int flat_attn_fwd_blocksparse(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
                               const int* tile_offsets, const int* tile_ids, int n_tile_ids, void* stream) {
-    const int rc = check_common(Q, K, V, O, B, H, N, d, scale, FLAT_MASK_NONE, 2);
+    const int rc = check_common(Q, K, V, O, B, H, N, d, scale, FLAT_MASK_NONE, 2, true);
     if (rc != FLAT_OK) return rc;
     if (!tile_offsets || !tile_ids) return FLAT_ERR_NULL;
     if (N > FLAT_SPARSE_BLOCK_KEYS * 2048) return FLAT_ERR_SHAPE;  // a row block's list must fit its LDS copy
@@ -139,7 +144,7 @@ int flat_attn_tile_shape_count(int d) { return flat::tile_shape_count(d); }
 
 int flat_attn_tile_shape_get(int d, int index, flat_tile_shape* out) {
     if (!out) return FLAT_ERR_NULL;
-    if (d != 64 && d != 128) return FLAT_ERR_UNSUPPORTED;
+    if (!fused_bf16_head_dim(d)) return FLAT_ERR_UNSUPPORTED;
     flat::TileShape t;
     if (!flat::tile_shape(d, index, &t)) return FLAT_ERR_SHAPE;
     out->d = t.d;
@@ -153,7 +158,7 @@ int flat_attn_tile_shape_get(int d, int index, flat_tile_shape* out) {
 }
 
 int flat_attn_tile_shape_occupancy(int d, int index) {
-    if (d != 64 && d != 128) return FLAT_ERR_UNSUPPORTED;
+    if (!fused_bf16_head_dim(d)) return FLAT_ERR_UNSUPPORTED;
     if (index < 0 || index >= flat::tile_shape_count(d)) return FLAT_ERR_SHAPE;
     int n = 0;
     return flat::tile_shape_occupancy(d, index, &n) == hipSuccess ? n : FLAT_ERR_HIP;
@@ -161,7 +166,7 @@ int flat_attn_tile_shape_occupancy(int d, int index) {
 
 int flat_attn_fwd_tile(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
                        int mask_kind, int tile_shape, void* stream) {
-    const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 2);
+    const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 2, true);
     if (rc != FLAT_OK) return rc;
     if ((unsigned long long)N * (unsigned)d * 2u > 0xffffffffULL) return FLAT_ERR_SHAPE;
     if (tile_shape < 0 || tile_shape >= flat::tile_shape_count(d)) return FLAT_ERR_SHAPE;
@@ -211,7 +216,8 @@ const char* flat_attn_status_string(int status) {
         case FLAT_ERR_NULL: return "FLAT_ERR_NULL: a required pointer is NULL";
         case FLAT_ERR_SHAPE: return "FLAT_ERR_SHAPE: B, H or N not positive, or the problem is too large to index";
         case FLAT_ERR_UNSUPPORTED:
-            return "FLAT_ERR_UNSUPPORTED: d must be 64 or 128, mask_kind 0 or 1, scale finite and >= 0, Nk >= Nq with the causal mask";
+            return "FLAT_ERR_UNSUPPORTED: d must be 32, 64, 96, 128 or 256 (64 or 128 for the fp32 and unfused paths), mask_kind 0 or 1, "
+                   "scale finite and >= 0, Nk >= Nq with the causal mask";
         case FLAT_ERR_ALIGN: return "FLAT_ERR_ALIGN: pointers must be 16-byte aligned";
         case FLAT_ERR_WORKSPACE: return "FLAT_ERR_WORKSPACE: workspace smaller than flat_attn_unfused_workspace_bytes()";
         case FLAT_ERR_HIP: return "FLAT_ERR_HIP: the HIP runtime refused a launch";
@@ -220,6 +226,6 @@ const char* flat_attn_status_string(int status) {
     }
 }
 
-int flat_attn_version(void) { return 200; }
+int flat_attn_version(void) { return 300; }
 
 }  // extern "C"

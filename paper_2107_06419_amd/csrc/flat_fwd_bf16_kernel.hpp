@@ -34,7 +34,12 @@ namespace flat {
 
 constexpr float kSumJump = 16384.0f;  // per lane and 32-key block: 16 probabilities
 
-// LDS tile layout.  Rows are stored unpadded (ROWB = 2 D bytes) because tiles arrive by
+// Head dimensions.  D is the head dimension of the tensors in memory (32, 64, 96, 128 or 256); the tiles in LDS
+// and the matrix products use DP = D rounded up to a power of two (96 -> 128: the missing columns of Q are zero,
+// so whatever the padded K columns hold drops out of the logits, and the padded output columns are not stored).
+// A tile holds BC keys: 64 (two 32-key blocks), or 32 at d = 256, where 64 keys of K and V would take 64 KiB.
+//
+// LDS tile layout.  Rows are stored unpadded (ROWB = 2 DP bytes) because tiles arrive by
 // global_load_lds_dwordx4, which writes the 64 lanes of a wavefront to 1024 contiguous LDS bytes
 // (lane l at base + 16 l).  Bank conflicts are avoided instead by an XOR swizzle of the 16-byte
 // chunk index within a row: chunk c of row r lives in slot c ^ swz(r).  The LDS serves 256 bytes
@@ -42,18 +47,24 @@ constexpr float kSumJump = 16384.0f;  // per lane and 32-key block: 16 probabili
 // touches 4 rows x 64 bytes; swz() is chosen so that both patterns hit every bank once.
 template <int D, int STAGES, int NW>
 struct Bf16Cfg {
-    static constexpr int BC = 64;                     // keys per tile
-    static constexpr int ROWB = D * 2;                // bytes per row
-    static constexpr int CHUNKS = ROWB / 16;          // 16-byte chunks per row
+    static_assert(D == 32 || D == 64 || D == 96 || D == 128 || D == 256, "head dimension not built");
+    static constexpr int DP = D == 96 ? 128 : D;      // head dimension of the tiles and products
+    static constexpr int BC = D == 256 ? 32 : 64;     // keys per tile
+    static constexpr int ROWB = DP * 2;               // bytes per row in LDS
+    static constexpr int GROWB = D * 2;               // bytes per row in global memory
+    static constexpr int CHUNKS = ROWB / 16;          // 16-byte chunks per LDS row
+    static constexpr int GCHUNKS = GROWB / 16;        // ... of which this many exist in memory
     static constexpr int KBYTES = BC * ROWB;
     static constexpr int VBYTES = BC * ROWB;
     static constexpr int STAGE = KBYTES + VBYTES;
     static constexpr int ROWS_PER_LOAD = 1024 / ROWB; // rows covered by one wave-wide 16-byte-per-lane load
     static constexpr int LOADS = BC / ROWS_PER_LOAD / NW; // such loads per wavefront per tensor per tile
+    static_assert(LOADS >= 1 && LOADS * ROWS_PER_LOAD * NW == BC, "the wavefronts must share a tile's rows evenly");
     static constexpr int LDS_BYTES = STAGES * STAGE;
     __device__ static __forceinline__ int swz(int r) {
-        if (D == 64) return (((r >> 1) & 1) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1);  // 128-byte rows: 2 rows per 256 B
-        return ((r & 3) << 2) | ((r >> 2) & 3);                                              // 256-byte rows
+        if (ROWB == 64) return (r >> 2) & 3;                                                    // 4 rows per 256 B
+        if (ROWB == 128) return (((r >> 1) & 1) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1);  // 2 rows per 256 B
+        return ((r & 3) << 2) | ((r >> 2) & 3);                                                 // rows of 256 B or more
     }
 };
 
@@ -77,19 +88,22 @@ __device__ __forceinline__ void wait_vm() {
 
 constexpr int kMaxSparseTiles = 2048;  // block-sparse: listed tiles per row block that fit the LDS copy of the list (8 KiB)
 
-// Template parameters: D head dimension, QB 32-row blocks per wavefront, NW wavefronts per workgroup, STAGES
+// Template parameters: D head dimension (32, 64, 96, 128, 256), QB 32-row blocks per wavefront, NW wavefronts per workgroup, STAGES
 // depth of the K/V ring, CAUSAL mask, SPARSE block-sparse variant (the workgroup visits only the 64-key tiles
 // listed for its row block, ids ascending, staged in LDS behind the ring; everything else as in the dense kernel).
-// Two wavefronts per SIMD (256 registers each), except 64 rows per wavefront at d = 128, whose accumulators alone
-// need more: that shape runs one wavefront per SIMD with the full 512 registers.
+// Two wavefronts per SIMD (256 registers each), except 64 rows per wavefront at d = 128 and every shape at d = 256,
+// whose accumulators alone need more: those run one wavefront per SIMD with the full 512 registers.
 
 template <int D, int QB, int NW, int STAGES, bool CAUSAL, bool SPARSE = false>
-__global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf16_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
+__global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 2) void fwd_bf16_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                           const bf16* __restrict__ V, bf16* __restrict__ O,
                                                           const Bf16Problem prob, int n_qtiles, int n_blocks,
                                                           int blocks_per_xcd, float c) {
     using C = Bf16Cfg<D, STAGES, NW>;
-    constexpr int QW = 32 * QB, BR = NW * QW, BC = C::BC, DS = D / 16, DB = D / 32;
+    constexpr int DP = C::DP, QW = 32 * QB, BR = NW * QW, BC = C::BC, DS = DP / 16, DB = DP / 32;
+    constexpr int KB = BC / 32;    // 32-key blocks per tile
+    constexpr int KB64 = 64 / BC;  // tiles per 64 keys (the unit of a block-sparse list)
+    static_assert(KB == 2 || STAGES % 2 == 0, "with one block per tile the unrolled loop needs an even ring");
     constexpr int LOADS_PER_TILE = 2 * C::LOADS;  // DMA instructions per wavefront per tile (K and V)
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -145,8 +159,8 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
         const int row = q0w + 32 * qb + l32;
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) {
-            uint4v z = {0, 0, 0, 0};
-            if (row < Nq) z = *(const uint4v*)(Qh + (size_t)row * D + ds * 16 + half * 8);
+            uint4v z = {0, 0, 0, 0};  // rows past the end and the padded head-dim columns are zero
+            if (row < Nq && ds * 16 + half * 8 < D) z = *(const uint4v*)(Qh + (size_t)row * D + ds * 16 + half * 8);
             qf[qb][ds] = __builtin_bit_cast(bf16x8, z);
         }
     }
@@ -156,25 +170,30 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
     int* const sp_ids = (int*)(smem + C::LDS_BYTES);
     int sp_count = 0;
     if (SPARSE) {
-        const int n_ktiles = (N + BC - 1) / BC;
-        const int row_block = bh * n_qtiles + qt;
+        const int n_ktiles = (N + 63) / 64;  // list entries name 64-key tiles
+        const int row_block = bh * ((Nq + 255) / 256) + (qt * BR) / 256;  // lists are per 256 query rows; BR divides 256
         const int lo = max(0, min(prob.n_tile_ids, prob.tile_offsets[row_block]));
         const int hi = max(lo, min(prob.n_tile_ids, prob.tile_offsets[row_block + 1]));
         sp_count = min(hi - lo, kMaxSparseTiles);
         for (int i = tid; i < sp_count; i += 64 * NW) sp_ids[i] = max(0, min(n_ktiles - 1, prob.tile_ids[lo + i]));
         __syncthreads();
     }
-    auto tile_of = [&](int j) __attribute__((always_inline)) { return SPARSE ? sp_ids[j] : j; };  // j-th tile this workgroup visits
+    // j-th tile this workgroup visits (a listed 64-key tile is KB64 consecutive tiles)
+    auto tile_of = [&](int j) __attribute__((always_inline)) {
+        if (!SPARSE) return j;
+        return KB64 == 1 ? sp_ids[j] : sp_ids[j / KB64] * KB64 + j % KB64;
+    };
 
     // reference max of each row = c * (q . k_first), k_first = the first key the row block sees (key 0 unless
     // block-sparse), from the fragments already in registers
     float m[QB];
     {
         float k0[DS][8];
-        const int first_key = (SPARSE && sp_count > 0) ? sp_ids[0] * BC : 0;
+        const int first_key = (SPARSE && sp_count > 0) ? sp_ids[0] * 64 : 0;
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) {
-            const uint4v kv = *(const uint4v*)(Kh + (size_t)first_key * C::ROWB + ds * 32 + half * 16);
+            uint4v kv = {0, 0, 0, 0};
+            if (ds * 16 + half * 8 < D) kv = *(const uint4v*)(Kh + (size_t)first_key * C::GROWB + ds * 32 + half * 16);
             const bf16x8 kb8 = __builtin_bit_cast(bf16x8, kv);
 #pragma unroll
             for (int e = 0; e < 8; ++e) k0[ds][e] = (float)kb8[e];
@@ -203,18 +222,21 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
 
     int kv_len = N;
     if (CAUSAL) kv_len = min(N, qt * BR + BR + off);
-    const int n_tiles = SPARSE ? sp_count : (kv_len + BC - 1) / BC;  // tiles this workgroup visits
+    const int n_tiles = SPARSE ? sp_count * KB64 : (kv_len + BC - 1) / BC;  // tiles this workgroup visits
 
     // ---- global -> LDS streaming.  Wave w issues load i of a tile for the 1024-byte LDS block
     // (NW i + w); lane l fills slot (l % CHUNKS) of row (l / CHUNKS) of that block, so it fetches
-    // the chunk whose swizzled position that is.  Keys beyond N are clamped to the last key: their
-    // logits are masked and their (finite) values meet a zero probability.
+    // the chunk whose swizzled position that is (for a padded head dimension, a chunk that does not
+    // exist in memory is replaced by one of the same row that does: its content never matters).
+    // Keys beyond N are clamped to the last key: their logits are masked and their (finite) values
+    // meet a zero probability.
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
     int ld_row[C::LOADS], ld_chunk_off[C::LOADS];
 #pragma unroll
     for (int i = 0; i < C::LOADS; ++i) {
         ld_row[i] = (NW * i + wave) * C::ROWS_PER_LOAD + lane / C::CHUNKS;
-        ld_chunk_off[i] = ((lane % C::CHUNKS) ^ C::swz(ld_row[i])) * 16;
+        const int chunk = (lane % C::CHUNKS) ^ C::swz(ld_row[i]);
+        ld_chunk_off[i] = (chunk < C::GCHUNKS ? chunk : chunk - (C::CHUNKS - C::GCHUNKS)) * 16;
     }
     auto issue_tile_loads = [&](int j, int stage) __attribute__((always_inline)) {  // j-th visited tile, stage = j % STAGES
         const uint32_t stage_base = smem_base + (uint32_t)stage * C::STAGE;
@@ -222,7 +244,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
 #pragma unroll
         for (int i = 0; i < C::LOADS; ++i) {
             const int key = min(tile * BC + ld_row[i], N - 1);
-            const uint32_t voff = (uint32_t)key * C::ROWB + ld_chunk_off[i];
+            const uint32_t voff = (uint32_t)key * C::GROWB + ld_chunk_off[i];
             const uint32_t lds_k = __builtin_amdgcn_readfirstlane(stage_base + (NW * i + wave) * 1024);
             dma16(Kh, voff, lds_k);
             dma16(Vh, voff, lds_k + C::KBYTES);
@@ -370,7 +392,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
 
     // With d = 128 two sets of V fragments do not fit the register file next to the accumulators: then one
     // set is used, refilled in the middle of each step right after the MFMAs that consumed it were issued.
-    constexpr bool kTwoVSets = (D == 64);
+    constexpr bool kTwoVSets = (DP <= 64);
     // Pipeline state: xA/xB hold the logits of the current / next block, pA/pB and vfA/vfB the
     // probabilities and V fragments of the block whose Attend is still owed.
     floatx16 xA[QB], xB[QB];
@@ -395,8 +417,8 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
     //   before step 2j+1: start streaming tile j+STAGES-1 into the stage that held tile j-1
     auto step = [&](int blk, int stage, int next_stage, bool masked, floatx16 (&xc)[QB], floatx16 (&xn)[QB], const uint32_t (&pp)[QB][8],
                     const bf16x8 (&vp)[2][DB], uint32_t (&pc)[QB][8], bf16x8 (&vc)[2][DB]) __attribute__((always_inline)) {
-        read_k(next_stage, (blk + 1) & 1, kf);
-        if (kTwoVSets) read_v(stage, blk & 1, vc);
+        read_k(next_stage, (blk + 1) & (KB - 1), kf);
+        if (kTwoVSets) read_v(stage, blk & (KB - 1), vc);
         __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads at the top: they have a whole step to land
         float bsum[QB];
         constexpr int kMfmaPerStep = 2 * QB * DB + QB * DS, kValuPerMfma = (QB * 48) / kMfmaPerStep;
@@ -421,7 +443,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
                 __builtin_amdgcn_sched_group_barrier(0x002, (QB * 16) / (2 * QB * DB), 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-            read_v(stage, blk & 1, vc);
+            read_v(stage, blk & (KB - 1), vc);
             __builtin_amdgcn_sched_barrier(0);
             logits(kf, xn);
             softmax_b(xc, pc, bsum);
@@ -445,57 +467,96 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
             lsum[qb] += bsum[qb];
         }
     };
-    auto tile_steps = [&](int j, int sj, bool masked) __attribute__((always_inline)) {  // sj = j % STAGES
-        const int sn = sj + 1 == STAGES ? 0 : sj + 1;       // stage of tile j+1
-        const int sd = sj == 0 ? STAGES - 1 : sj - 1;       // stage of tile j-1 = target of tile j+STAGES-1
-        // first 32-key block of the tile, as a key position / 32 (only the masked form of a step looks at it)
-        const int kb0 = 2 * ((SPARSE && masked) ? tile_of(j) : j);
-        if (kTwoVSets)
-            step(kb0, sj, sj, masked, xA, xB, pB, vfB, pA, vfA);
-        else
-            step(kb0, sj, sj, masked, xA, xB, pB, vfA, pA, vfA);
-        if (j + STAGES - 2 < n_tiles)
-            wait_vm<(STAGES - 3) * LOADS_PER_TILE>();
-        else
-            wait_vm<0>();
-        __syncthreads();
-        if (j + STAGES - 1 < n_tiles) issue_tile_loads(j + STAGES - 1, sd);
-        if (kTwoVSets)
-            step(kb0 + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfB);
-        else
-            step(kb0 + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfA);
-    };
-
-    // Per wavefront the tiles fall into three consecutive ranges: fully visible, partly masked
-    // (sequence tail or causal diagonal), and not visible at all (the wavefront then only keeps
-    // streaming and synchronising for the others).
-    const int n_vis_blocks = (N + 31) / 32;
-    // (block-sparse: the list is ascending, so only its last tile can be the ragged end of the sequence)
-    const int n_unm_tiles = SPARSE ? max(n_tiles - 1, 0) : (CAUSAL ? min((q0w + off + 1) / 32, N / 32) : N / 32) / 2;
-    const int n_act_tiles = SPARSE ? n_tiles : ((CAUSAL ? min(n_vis_blocks, (q0w + QW - 1 + off) / 32 + 1) : n_vis_blocks) + 1) / 2;
-    int j = 0;
-    // main loop: STAGES fully visible tiles per trip, so that every ring stage index is a constant
-#pragma unroll 1
-    for (; j + STAGES <= n_unm_tiles; j += STAGES) {
-#pragma unroll
-        for (int sj = 0; sj < STAGES; ++sj) tile_steps(j + sj, sj, false);
-    }
-    // remaining visible tiles and the partly masked ones (masking a fully visible tile changes nothing)
-    int sj = 0;  // j is a multiple of STAGES here
-#pragma unroll 1
-    for (; j < n_act_tiles; ++j) {
-        tile_steps(j, sj, true);
-        sj = sj + 1 == STAGES ? 0 : sj + 1;
-    }
-    attend(kTwoVSets ? vfB : vfA, pB);  // the Attend still owed for the last block
-#pragma unroll 1
-    for (; j < n_tiles; ++j) {
+    // Ring bookkeeping around the steps of one tile.  sync_before_last_step: wait for tile j+1 (of the tiles in
+    // flight only STAGES-3 may still be outstanding), barrier (every wavefront is then also past its last read of
+    // tile j-1), and start streaming tile j+STAGES-1 into the stage that held tile j-1.
+    auto sync_and_stream = [&](int j, int sj) __attribute__((always_inline)) {
         if (j + STAGES - 2 < n_tiles)
             wait_vm<(STAGES - 3) * LOADS_PER_TILE>();
         else
             wait_vm<0>();
         __syncthreads();
         if (j + STAGES - 1 < n_tiles) issue_tile_loads(j + STAGES - 1, sj == 0 ? STAGES - 1 : sj - 1);
+    };
+    // Two blocks per tile: the second step already reads K of the next tile, so the synchronisation sits between
+    // the two steps.  One block per tile: it sits before the tile's only step, and consecutive tiles alternate the
+    // roles of the two logit / probability register sets (`odd`).
+    auto tile_steps = [&](int j, int sj, bool masked, bool odd) __attribute__((always_inline)) {  // sj = j % STAGES
+        const int sn = sj + 1 == STAGES ? 0 : sj + 1;       // stage of tile j+1
+        // first 32-key block of the tile, as a key position / 32 (only the masked form of a step looks at it)
+        const int kb0 = KB * ((SPARSE && masked) ? tile_of(j) : j);
+        if (KB == 2) {
+            if (kTwoVSets)
+                step(kb0, sj, sj, masked, xA, xB, pB, vfB, pA, vfA);
+            else
+                step(kb0, sj, sj, masked, xA, xB, pB, vfA, pA, vfA);
+            sync_and_stream(j, sj);
+            if (kTwoVSets)
+                step(kb0 + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfB);
+            else
+                step(kb0 + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfA);
+        } else {
+            sync_and_stream(j, sj);
+            if (!odd) {
+                if (kTwoVSets)
+                    step(kb0, sj, sn, masked, xA, xB, pB, vfB, pA, vfA);
+                else
+                    step(kb0, sj, sn, masked, xA, xB, pB, vfA, pA, vfA);
+            } else {
+                if (kTwoVSets)
+                    step(kb0, sj, sn, masked, xB, xA, pA, vfA, pB, vfB);
+                else
+                    step(kb0, sj, sn, masked, xB, xA, pA, vfA, pB, vfA);
+            }
+        }
+    };
+
+    // Per wavefront the tiles fall into three consecutive ranges: fully visible, partly masked
+    // (sequence tail or causal diagonal), and not visible at all (the wavefront then only keeps
+    // streaming and synchronising for the others).
+    const int n_vis_blocks = (N + 31) / 32;
+    // (block-sparse: the list is ascending, so only its last 64 keys can hold the ragged end of the sequence)
+    const int n_unm_tiles = SPARSE ? max(n_tiles - KB64, 0) : (CAUSAL ? min((q0w + off + 1) / 32, N / 32) : N / 32) / KB;
+    const int n_act_tiles =
+        SPARSE ? n_tiles : ((CAUSAL ? min(n_vis_blocks, (q0w + QW - 1 + off) / 32 + 1) : n_vis_blocks) + KB - 1) / KB;
+    int j = 0;
+    // main loop: STAGES fully visible tiles per trip, so that every ring stage index is a constant
+#pragma unroll 1
+    for (; j + STAGES <= n_unm_tiles; j += STAGES) {
+#pragma unroll
+        for (int sj = 0; sj < STAGES; ++sj) tile_steps(j + sj, sj, false, (sj & 1) != 0);
+    }
+    // remaining visible tiles and the partly masked ones (masking a fully visible tile changes nothing)
+    int sj = 0;  // j is a multiple of STAGES here (even, where that matters)
+    bool owed_in_a = false;  // one block per tile only: the last step left its probabilities in pA, not pB
+    if (KB == 2) {
+#pragma unroll 1
+        for (; j < n_act_tiles; ++j) {
+            tile_steps(j, sj, true, false);
+            sj = sj + 1 == STAGES ? 0 : sj + 1;
+        }
+    } else {
+#pragma unroll 1
+        for (; j < n_act_tiles; j += 2) {
+            tile_steps(j, sj, true, false);
+            sj = sj + 1 == STAGES ? 0 : sj + 1;
+            if (j + 1 < n_act_tiles) {
+                tile_steps(j + 1, sj, true, true);
+                sj = sj + 1 == STAGES ? 0 : sj + 1;
+            } else {
+                owed_in_a = true;
+            }
+        }
+        if (j > n_act_tiles) j = n_act_tiles;
+    }
+    // the Attend still owed for the last block
+    if (owed_in_a)
+        attend(kTwoVSets ? vfA : vfA, pA);
+    else
+        attend(kTwoVSets ? vfB : vfA, pB);
+#pragma unroll 1
+    for (; j < n_tiles; ++j) {
+        sync_and_stream(j, sj);
         sj = sj + 1 == STAGES ? 0 : sj + 1;
     }
 
@@ -511,6 +572,7 @@ __global__ __launch_bounds__(64 * NW, (D == 128 && QB == 2) ? 1 : 2) void fwd_bf
 #pragma unroll
                 for (int rq = 0; rq < 4; ++rq) {
                     const int dcol = 32 * db + 8 * rq + 4 * half;
+                    if (32 * db + 8 * rq >= D) continue;  // padded head-dim columns
                     floatx2 w;
                     w[0] = __builtin_bit_cast(float, pack_bf16(oacc[qb][db][4 * rq] * inv, oacc[qb][db][4 * rq + 1] * inv));
                     w[1] = __builtin_bit_cast(float, pack_bf16(oacc[qb][db][4 * rq + 2] * inv, oacc[qb][db][4 * rq + 3] * inv));

@@ -20,17 +20,32 @@ struct Entry {
 
 template <int D, int QB, int NW, int STAGES>
 constexpr Entry entry() {
-    return Entry{TileShape{D, 32 * QB * NW, 64, NW, 32 * QB, STAGES, STAGES * 2 * 64 * D * 2},
+    constexpr int DP = D == 96 ? 128 : D, BC = D == 256 ? 32 : 64;  // as in Bf16Cfg: padded row length, keys per tile
+    return Entry{TileShape{D, 32 * QB * NW, BC, NW, 32 * QB, STAGES, STAGES * 2 * BC * DP * 2},
                  &launch_fwd_bf16_shape<D, QB, NW, STAGES>, &fwd_bf16_shape_occupancy<D, QB, NW, STAGES>};
 }
 
 const Entry kD64[] = {entry<64, 2, 4, 4>(), entry<64, 2, 4, 3>(), entry<64, 2, 4, 6>(), entry<64, 2, 8, 4>(),
                       entry<64, 1, 8, 4>(), entry<64, 1, 4, 4>(), entry<64, 2, 2, 4>(), entry<64, 1, 4, 3>()};
 const Entry kD128[] = {entry<128, 1, 8, 3>(), entry<128, 1, 8, 4>(), entry<128, 1, 4, 3>(), entry<128, 2, 4, 3>()};
+const Entry kD32[] = {entry<32, 2, 4, 4>()};
+const Entry kD96[] = {entry<96, 1, 8, 3>()};
+const Entry kD256[] = {entry<256, 1, 4, 4>()};
+
+const Entry* table(int d) {
+    switch (d) {
+        case 32: return kD32;
+        case 64: return kD64;
+        case 96: return kD96;
+        case 128: return kD128;
+        case 256: return kD256;
+        default: return nullptr;
+    }
+}
 
 const Entry* find(int d, int index) {
     if (index < 0 || index >= tile_shape_count(d)) return nullptr;
-    return d == 64 ? &kD64[index] : &kD128[index];
+    return &table(d)[index];
 }
 
 }  // namespace
@@ -38,6 +53,9 @@ const Entry* find(int d, int index) {
 int tile_shape_count(int d) {
     if (d == 64) return (int)(sizeof(kD64) / sizeof(kD64[0]));
     if (d == 128) return (int)(sizeof(kD128) / sizeof(kD128[0]));
+    if (d == 32) return (int)(sizeof(kD32) / sizeof(kD32[0]));
+    if (d == 96) return (int)(sizeof(kD96) / sizeof(kD96[0]));
+    if (d == 256) return (int)(sizeof(kD256) / sizeof(kD256[0]));
     return 0;
 }
 

@@ -54,7 +54,11 @@ def test_validation_happens_before_any_gpu_work():
 
     assert fwd(Q=None) == -1 and fwd(K=None) == -1 and fwd(V=None) == -1 and fwd(O=None) == -1
     assert fwd(B=0) == -2 and fwd(H=-1) == -2 and fwd(N=0) == -2
-    assert fwd(d=32) == -3 and fwd(d=96) == -3 and fwd(mask=2) == -3 and fwd(mask=-1) == -3
+    assert fwd(d=48) == -3 and fwd(d=80) == -3 and fwd(d=512) == -3 and fwd(d=0) == -3 and fwd(mask=2) == -3 and fwd(mask=-1) == -3
+    for d_ok in (32, 64, 96, 128, 256):   # every head dimension the fused bf16 kernel is built for gets past the d check
+        assert fwd(d=d_ok, B=0) == -2
+        assert fwd(d=d_ok, Q=ok[0] + 8) == -4
+        assert lib.flat_attn_fwd_f32(ok[0] + 8, ok[1], ok[2], ok[3], 1, 1, 8, d_ok, 1.0, 0, None) == (-4 if d_ok in (64, 128) else -3)
     assert fwd(scale=-0.5) == -3 and fwd(scale=float("inf")) == -3 and fwd(scale=float("nan")) == -3
     assert fwd(Q=ok[0] + 8) == -4 and fwd(O=ok[3] + 2) == -4
     assert fwd(O=ok[0]) == -7 and fwd(O=ok[1] + 16) == -7
@@ -85,18 +89,20 @@ def test_tile_shape_table_is_consistent():
     """The shape table is host data: index 0 is the default, every entry describes a launchable shape, and
     out-of-range queries are refused without touching a GPU."""
     lib = fa.load_library()
-    assert fa.flat_attn_tile_shape_count(32) == 0 and fa.flat_attn_tile_shape_count(96) == 0
-    for d in (64, 128):
+    assert fa.flat_attn_tile_shape_count(48) == 0 and fa.flat_attn_tile_shape_count(512) == 0
+    for d in (32, 64, 96, 128, 256):
         n = fa.flat_attn_tile_shape_count(d)
-        assert n >= 2
+        assert n >= (2 if d in (64, 128) else 1)
         seen = set()
         for idx in range(n):
             t = fa.flat_attn_tile_shape_get(d, idx).as_dict()
-            assert t["d"] == d and t["keys_per_tile"] == 64
+            assert t["d"] == d and t["keys_per_tile"] == (32 if d == 256 else 64)
             assert t["rows_per_workgroup"] == t["wavefronts"] * t["rows_per_wavefront"]
             assert t["rows_per_wavefront"] in (32, 64) and 1 <= t["wavefronts"] <= 16
             assert t["lds_stages"] >= 3
-            assert t["lds_bytes"] == t["lds_stages"] * 2 * t["keys_per_tile"] * d * 2 <= 160 * 1024  # K and V tiles, bf16
+            d_lds = 128 if d == 96 else d  # rows of 96 elements are padded to 128 in LDS
+            assert t["lds_bytes"] == t["lds_stages"] * 2 * t["keys_per_tile"] * d_lds * 2 <= 160 * 1024  # K and V tiles, bf16
+            assert 256 % t["rows_per_workgroup"] == 0 or t["rows_per_workgroup"] % 256 == 0
             key = (t["rows_per_workgroup"], t["wavefronts"], t["lds_stages"])
             assert key not in seen
             seen.add(key)
@@ -107,7 +113,7 @@ def test_tile_shape_table_is_consistent():
             assert lib.flat_attn_fwd_tile(0x1000, 1 << 40, 2 << 40, 3 << 40, 1, 1, 8, d, 1.0, 0, bad, None) == -2
             assert lib.flat_attn_tile_shape_occupancy(d, bad) == -2
     assert lib.flat_attn_tile_shape_get(64, 0, None) == -1
-    assert lib.flat_attn_tile_shape_occupancy(96, 0) == -3
+    assert lib.flat_attn_tile_shape_occupancy(80, 0) == -3
     d64, d128 = fa.flat_attn_tile_shape_get(64, 0).as_dict(), fa.flat_attn_tile_shape_get(128, 0).as_dict()
     assert (d64["rows_per_workgroup"], d64["wavefronts"], d64["lds_stages"]) == (256, 4, 4)
     assert (d128["rows_per_workgroup"], d128["wavefronts"], d128["lds_stages"]) == (256, 8, 3)
@@ -139,7 +145,7 @@ def test_blocksparse_entry_point_validation():
 
     assert sp(Q=None) == -1 and sp(offs=None) == -1 and sp(ids=None) == -1
     assert sp(N=0) == -2 and sp(N=131072 + 1) == -2 and sp(n=-1) == -2
-    assert sp(d=96) == -3 and sp(scale=-1.0) == -3
+    assert sp(d=80) == -3 and sp(scale=-1.0) == -3
     assert sp(offs=0x9002) == -4 and sp(ids=0xA001) == -4 and sp(V=far[2] + 8) == -4
     assert sp(O=far[0]) == -7 and sp(offs=far[3] + 64) == -7 and sp(ids=far[3] + 128) == -7
 

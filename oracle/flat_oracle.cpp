@@ -172,7 +172,7 @@ int flat_oracle_attention(const double* Q, const double* K, const double* V, dou
 //   * mask_kind 1 (causal): the queries are the last Nq positions of the key sequence, so key j contributes to
 //     query i iff j <= i + (Nk - Nq); needs Nk >= Nq.  With kv_lens the alignment still refers to Nk.
 //   In every case the visible keys of a row are a prefix 0 .. n-1 of the key sequence, n >= 1.
-// Pins (tests/test_oracle_pins.py): equals flat_oracle_attention when Nq = Nk and kv_lens is null; the last Nq
+// Pins (tests/test_oracle_cross_pins.py): equals flat_oracle_attention when Nq = Nk and kv_lens is null; the last Nq
 // rows of causal self-attention over Nk positions; attention over K, V truncated to kv_lens[b]; brute force
 // over explicit visibility tests on tiny shapes.
 int flat_oracle_attention_cross(const double* Q, const double* K, const double* V, double* O, int B, int H, int64_t Nq,

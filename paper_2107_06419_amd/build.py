@@ -24,9 +24,15 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+# Checking build: the fused bf16 kernels with every ring phase fully synchronised (FLAT_SYNC_EVERY_PHASE), linked
+# with the unchanged remaining objects into a second library that a GPU test compares bit for bit with the first.
+SYNC_LIB = os.path.join(HERE, "libflat_attn_sync.so")
+SYNC_SOURCES = [s for s in SOURCES if s.startswith("flat_fwd_bf16")]
+
+
+def _compile(src: str, sync: bool = False) -> str:
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + (".sync.o" if sync else ".o"))
+    cmd = [_hipcc(), *FLAGS, *(["-DFLAT_SYNC_EVERY_PHASE"] if sync else []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
@@ -40,12 +46,16 @@ def build_library(verbose: bool = True) -> str:
     """Compile every kernel source for gfx950 and link the shared library. Always recompiles."""
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=8) as pool:
-        objs = list(pool.map(_compile, SOURCES))
-    tmp = LIB + f".tmp{os.getpid()}"
-    subprocess.check_call([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
-    os.replace(tmp, LIB)
-    if verbose:
-        print(f"built {LIB}")
+        jobs = [pool.submit(_compile, s) for s in SOURCES] + [pool.submit(_compile, s, True) for s in SYNC_SOURCES]
+        objs = [j.result() for j in jobs]
+    plain, sync = objs[:len(SOURCES)], objs[len(SOURCES):]
+    sync_objs = [o for s, o in zip(SOURCES, plain) if s not in SYNC_SOURCES] + sync
+    for lib, parts in ((LIB, plain), (SYNC_LIB, sync_objs)):
+        tmp = lib + f".tmp{os.getpid()}"
+        subprocess.check_call([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *parts])
+        os.replace(tmp, lib)
+        if verbose:
+            print(f"built {lib}")
     return LIB
 
 

@@ -32,7 +32,7 @@ int check_common(const void* Q, const void* K, const void* V, const void* O, int
     if (!(scale >= 0.0f) || isinf(scale)) return FLAT_ERR_UNSUPPORTED;  // also rejects NaN
     // B*H must fit the grid; B*H*N*d*elem and B*H*N*N*4 must fit 63 bits
     const long long BH = (long long)B * H;
-    if (BH > 0x7fffffffLL / ((N + 127) / 128)) return FLAT_ERR_SHAPE;
+    if (BH > 0x7fffffffLL / (((long long)N + 127) / 128)) return FLAT_ERR_SHAPE;
     const unsigned __int128 tensor = (unsigned __int128)BH * (unsigned)N * (unsigned)d * elem;
     const unsigned __int128 square = (unsigned __int128)BH * (unsigned)N * (unsigned)N * 4u;
     const unsigned __int128 lim = (unsigned __int128)1 << 62;
@@ -68,7 +68,7 @@ int flat_attn_fwd_cross(const void* Q, const void* K, const void* V, void* O, in
     if (!(scale >= 0.0f) || isinf(scale)) return FLAT_ERR_UNSUPPORTED;
     if (mask_kind == FLAT_MASK_CAUSAL && Nk < Nq) return FLAT_ERR_UNSUPPORTED;  // some query would see no key
     const long long BH = (long long)B * H;
-    if (BH > 0x7fffffffLL / ((Nq + 127) / 128)) return FLAT_ERR_SHAPE;
+    if (BH > 0x7fffffffLL / (((long long)Nq + 127) / 128)) return FLAT_ERR_SHAPE;
     const unsigned long long per_head_q = (unsigned long long)Nq * (unsigned)d * 2u, per_head_k = (unsigned long long)Nk * (unsigned)d * 2u;
     if (per_head_q > 0xffffffffULL || per_head_k > 0xffffffffULL) return FLAT_ERR_SHAPE;  // 32-bit byte offsets within a head
     const unsigned __int128 qbytes128 = (unsigned __int128)BH * per_head_q, kbytes128 = (unsigned __int128)BH * per_head_k;

@@ -34,6 +34,16 @@ namespace flat {
 
 constexpr float kSumJump = 16384.0f;  // per lane and 32-key block: 16 probabilities
 
+// Checking build (-DFLAT_SYNC_EVERY_PHASE): nothing is left in flight across a phase of the ring.  Every
+// streaming load is awaited in full and fenced by a barrier on both sides, and every LDS operand read is awaited
+// before the step goes on.  The release build overlaps these phases and counts on its vmcnt arithmetic and on
+// one barrier per tile; the two builds must produce bit-identical results, which a GPU test checks.
+#ifdef FLAT_SYNC_EVERY_PHASE
+constexpr bool kSyncEveryPhase = true;
+#else
+constexpr bool kSyncEveryPhase = false;
+#endif
+
 // Head dimensions.  D is the head dimension of the tensors in memory (32, 64, 96, 128 or 256); the tiles in LDS
 // and the matrix products use DP = D rounded up to a power of two (96 -> 128: the missing columns of Q are zero,
 // so whatever the padded K columns hold drops out of the logits, and the padded output columns are not stored).
@@ -419,6 +429,7 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
                     const bf16x8 (&vp)[2][DB], uint32_t (&pc)[QB][8], bf16x8 (&vc)[2][DB]) __attribute__((always_inline)) {
         read_k(next_stage, (blk + 1) & (KB - 1), kf);
         if (kTwoVSets) read_v(stage, blk & (KB - 1), vc);
+        if (kSyncEveryPhase) __builtin_amdgcn_s_waitcnt((63 & 15) | ((63 >> 4) << 14) | (7 << 4) | (0 << 8));  // lgkmcnt(0) only
         __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads at the top: they have a whole step to land
         float bsum[QB];
         constexpr int kMfmaPerStep = 2 * QB * DB + QB * DS, kValuPerMfma = (QB * 48) / kMfmaPerStep;
@@ -444,6 +455,7 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
             }
             __builtin_amdgcn_sched_barrier(0);
             read_v(stage, blk & (KB - 1), vc);
+            if (kSyncEveryPhase) __builtin_amdgcn_s_waitcnt((63 & 15) | ((63 >> 4) << 14) | (7 << 4) | (0 << 8));
             __builtin_amdgcn_sched_barrier(0);
             logits(kf, xn);
             softmax_b(xc, pc, bsum);
@@ -471,12 +483,16 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
     // flight only STAGES-3 may still be outstanding), barrier (every wavefront is then also past its last read of
     // tile j-1), and start streaming tile j+STAGES-1 into the stage that held tile j-1.
     auto sync_and_stream = [&](int j, int sj) __attribute__((always_inline)) {
-        if (j + STAGES - 2 < n_tiles)
-            wait_vm<(STAGES - 3) * LOADS_PER_TILE>();
-        else
+        if (kSyncEveryPhase || j + STAGES - 2 >= n_tiles)
             wait_vm<0>();
+        else
+            wait_vm<(STAGES - 3) * LOADS_PER_TILE>();
         __syncthreads();
         if (j + STAGES - 1 < n_tiles) issue_tile_loads(j + STAGES - 1, sj == 0 ? STAGES - 1 : sj - 1);
+        if (kSyncEveryPhase) {  // every wavefront runs this the same number of times, so the barrier is safe here
+            wait_vm<0>();
+            __syncthreads();
+        }
     };
     // Two blocks per tile: the second step already reads K of the next tile, so the synchronisation sits between
     // the two steps.  One block per tile: it sits before the tile's only step, and consecutive tiles alternate the

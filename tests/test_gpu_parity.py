@@ -509,9 +509,13 @@ def test_status_codes_on_device_buffers():
     with pytest.raises(fa.FlatAttnError) as e:
         fa.flat_attn_unfused(t, t, t, o, 1.0, 0, ws)
     assert e.value.status == -5
-    t96 = torch.zeros(1, 1, 64, 96, dtype=torch.bfloat16, device="cuda")
+    t80 = torch.zeros(1, 1, 64, 80, dtype=torch.bfloat16, device="cuda")  # a head dimension the library is not built for
     with pytest.raises(fa.FlatAttnError) as e:
-        fa.flat_attn_fwd(t96, t96, t96, torch.zeros_like(t96), 1.0, 0)
+        fa.flat_attn_fwd(t80, t80, t80, torch.zeros_like(t80), 1.0, 0)
+    assert e.value.status == -3
+    t96 = torch.zeros(1, 1, 64, 96, dtype=torch.bfloat16, device="cuda")  # fused: built; unfused baseline: not
+    with pytest.raises(fa.FlatAttnError) as e:
+        fa.flat_attn_unfused(t96, t96, t96, torch.zeros_like(t96), 1.0, 0, torch.zeros(64 * 64, dtype=torch.float32, device="cuda"))
     assert e.value.status == -3
 
 

@@ -50,7 +50,7 @@ typedef enum {
     FLAT_ERR_SHAPE = -2,       /* B, H or N is not positive, or B*H*N*N / B*H*N*d overflows */
     FLAT_ERR_UNSUPPORTED = -3, /* head dimension not built, unknown mask_kind or dtype, scale negative or not finite, causal with Nk < Nq */
     FLAT_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
-    FLAT_ERR_WORKSPACE = -5,   /* workspace_bytes is smaller than flat_attn_unfused_workspace_bytes() */
+    FLAT_ERR_WORKSPACE = -5,   /* a workspace is smaller than the matching *_workspace_bytes() call says */
     FLAT_ERR_HIP = -6,         /* the HIP runtime refused a launch */
     FLAT_ERR_ALIAS = -7        /* O overlaps Q, K or V */
 } flat_status;
@@ -85,6 +85,28 @@ int flat_attn_fwd(const void* Q, const void* K, const void* V, void* O,
 int flat_attn_fwd_cross(const void* Q, const void* K, const void* V, void* O,
                         int B, int H, int Nq, int Nk, int d, float scale, int mask_kind,
                         const int* kv_lens, void* stream);
+
+/*
+ * flat_attn_fwd_cross for FEW query rows over MANY keys (a segment of new positions attending over a long cache:
+ * the TransformerXL case of the paper's workload list, section 6 "Workloads").  Section 5.3 weighs the row
+ * granularity by how well it fills the compute array; with only a handful of row blocks no tile size fills it,
+ * so here the key loop of every row block is divided over n_splits workgroups that leave partial results
+ * (reference maximum, row sum, unnormalised output, all fp32) in `workspace`, and a second kernel merges them.
+ * Same arguments, masks, key counts and tolerance as flat_attn_fwd_cross, plus
+ *   n_splits: parts the key sequence is divided into, clamped to [1, number of key tiles]; <= 0 lets the library
+ *     choose (about two workgroups per compute-unit slot, at least 8 key tiles per split).
+ *     flat_attn_fwd_splitkv_splits returns the number actually used (or a negative flat_status).
+ *   workspace: device, 16-byte aligned, at least flat_attn_fwd_splitkv_workspace_bytes() bytes (same B, H, Nq,
+ *     Nk, d, n_splits; 0 means the arguments are invalid), overwritten; it must not overlap any other buffer
+ *     (FLAT_ERR_ALIAS).  FLAT_ERR_WORKSPACE if too small.
+ * The result differs from flat_attn_fwd_cross in the last bits (different summation order), and is itself
+ * bitwise reproducible for a given n_splits.  Two launches (partial pass, merge) are enqueued on `stream`.
+ */
+int flat_attn_fwd_splitkv_splits(int B, int H, int Nq, int Nk, int d, int n_splits);
+size_t flat_attn_fwd_splitkv_workspace_bytes(int B, int H, int Nq, int Nk, int d, int n_splits);
+int flat_attn_fwd_splitkv(const void* Q, const void* K, const void* V, void* O,
+                          int B, int H, int Nq, int Nk, int d, float scale, int mask_kind,
+                          const int* kv_lens, int n_splits, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Block-sparse variant.  The paper asks (section 8.2, compatibility with sparse-attention accelerators) whether

@@ -57,6 +57,12 @@ def load_library():
     lib.flat_attn_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, vp]
     lib.flat_attn_fwd_cross.restype = i
     lib.flat_attn_fwd_cross.argtypes = [vp, vp, vp, vp, i, i, i, i, i, f, i, vp, vp]
+    lib.flat_attn_fwd_splitkv_splits.restype = i
+    lib.flat_attn_fwd_splitkv_splits.argtypes = [i, i, i, i, i, i]
+    lib.flat_attn_fwd_splitkv_workspace_bytes.restype = sz
+    lib.flat_attn_fwd_splitkv_workspace_bytes.argtypes = [i, i, i, i, i, i]
+    lib.flat_attn_fwd_splitkv.restype = i
+    lib.flat_attn_fwd_splitkv.argtypes = [vp, vp, vp, vp, i, i, i, i, i, f, i, vp, i, vp, sz, vp]
     lib.flat_attn_fwd_blocksparse.restype = i
     lib.flat_attn_fwd_blocksparse.argtypes = [vp, vp, vp, vp, i, i, i, i, f, vp, vp, i, vp]
     lib.flat_attn_fwd_f32.restype = i
@@ -152,6 +158,43 @@ def flat_attn_fwd_cross(Q, K, V, O, scale: float, mask_kind: int = FLAT_MASK_NON
         lens_ptr = kv_lens.data_ptr()
     _check(load_library().flat_attn_fwd_cross(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, Nq, Nk, d,
                                               float(scale), int(mask_kind), lens_ptr, _stream_handle(stream)))
+
+
+def flat_attn_fwd_splitkv_splits(B: int, H: int, Nq: int, Nk: int, d: int, n_splits: int = 0) -> int:
+    """Number of splits a flat_attn_fwd_splitkv call with these arguments uses (n_splits <= 0: the library's choice)."""
+    n = int(load_library().flat_attn_fwd_splitkv_splits(int(B), int(H), int(Nq), int(Nk), int(d), int(n_splits)))
+    if n < 0:
+        _check(n)
+    return n
+
+
+def flat_attn_fwd_splitkv_workspace_bytes(B: int, H: int, Nq: int, Nk: int, d: int, n_splits: int = 0) -> int:
+    return int(load_library().flat_attn_fwd_splitkv_workspace_bytes(int(B), int(H), int(Nq), int(Nk), int(d), int(n_splits)))
+
+
+def _cross_args(Q, K, V, O, kv_lens):
+    import torch
+    B, H, Nq, d = _dev_args(torch.bfloat16, Q, O)
+    Bk, Hk, Nk, dk = _dev_args(torch.bfloat16, K, V)
+    if (Bk, Hk, dk) != (B, H, d):
+        raise ValueError("K, V must share batch, heads and head size with Q")
+    lens_ptr = None
+    if kv_lens is not None:
+        if not kv_lens.is_cuda or kv_lens.dtype != torch.int32 or not kv_lens.is_contiguous() or kv_lens.numel() != B:
+            raise ValueError("kv_lens must be a contiguous int32 GPU tensor with one entry per batch")
+        lens_ptr = kv_lens.data_ptr()
+    return B, H, Nq, Nk, d, lens_ptr
+
+
+def flat_attn_fwd_splitkv(Q, K, V, O, scale: float, mask_kind: int, kv_lens, n_splits: int, workspace, stream=None) -> None:
+    """flat_attn_fwd_cross with the keys of every row block divided over n_splits workgroups (<= 0: library's choice);
+    `workspace` is a device tensor of at least flat_attn_fwd_splitkv_workspace_bytes() bytes."""
+    B, H, Nq, Nk, d, lens_ptr = _cross_args(Q, K, V, O, kv_lens)
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    _check(load_library().flat_attn_fwd_splitkv(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, Nq, Nk, d,
+                                                float(scale), int(mask_kind), lens_ptr, int(n_splits), workspace.data_ptr(),
+                                                workspace.numel() * workspace.element_size(), _stream_handle(stream)))
 
 
 FLAT_SPARSE_BLOCK_ROWS = 256

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflat_attn.so")
 SOURCES = ["flat_api.hip", "flat_fwd_bf16.hip", "flat_fwd_bf16_shapes_d64a.hip", "flat_fwd_bf16_shapes_d64b.hip",
-           "flat_fwd_bf16_shapes_d128.hip", "flat_fwd_bf16_shapes_dx.hip", "flat_tiles.hip", "flat_fwd_f32.hip", "flat_unfused.hip", "flat_probe.hip"]
+           "flat_fwd_bf16_shapes_d128.hip", "flat_fwd_bf16_shapes_dx.hip", "flat_splitkv.hip", "flat_plan.hip", "flat_tiles.hip", "flat_fwd_f32.hip", "flat_unfused.hip", "flat_probe.hip"]
 # packed fp32 VALU instructions are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
@@ -27,7 +27,7 @@ def _hipcc() -> str:
 # Checking build: the fused bf16 kernels with every ring phase fully synchronised (FLAT_SYNC_EVERY_PHASE), linked
 # with the unchanged remaining objects into a second library that a GPU test compares bit for bit with the first.
 SYNC_LIB = os.path.join(HERE, "libflat_attn_sync.so")
-SYNC_SOURCES = [s for s in SOURCES if s.startswith("flat_fwd_bf16")]
+SYNC_SOURCES = [s for s in SOURCES if s.startswith("flat_fwd_bf16") or s == "flat_splitkv.hip"]
 
 
 def _compile(src: str, sync: bool = False) -> str:

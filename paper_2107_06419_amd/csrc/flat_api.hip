@@ -43,24 +43,10 @@ int check_common(const void* Q, const void* K, const void* V, const void* O, int
     return FLAT_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-int flat_attn_fwd(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
-                  int mask_kind, void* stream) {
-    const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 2, true);
-    if (rc != FLAT_OK) return rc;
-    if ((unsigned long long)N * (unsigned)d * 2u > 0xffffffffULL) return FLAT_ERR_SHAPE;  // the kernel addresses one head with 32-bit byte offsets
-    const flat::Bf16Problem prob{N, N, 0, H, nullptr, nullptr, nullptr, 0};
-    const hipError_t e = flat::launch_fwd_bf16(Q, K, V, O, B * H, prob, d, scale, mask_kind == FLAT_MASK_CAUSAL,
-                                               static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
-}
-
-int flat_attn_fwd_cross(const void* Q, const void* K, const void* V, void* O, int B, int H, int Nq, int Nk, int d, float scale,
-                        int mask_kind, const int* kv_lens, void* stream) {
-    // the checks of check_common, with separate lengths for the query side (Q, O) and the key side (K, V)
+// The checks of check_common with separate lengths for the query side (Q, O) and the key side (K, V); on success
+// *qbytes / *kbytes are the sizes of one query-side / key-side tensor.
+int check_cross(const void* Q, const void* K, const void* V, const void* O, int B, int H, int Nq, int Nk, int d, float scale,
+                int mask_kind, const int* kv_lens, size_t* qbytes_out, size_t* kbytes_out) {
     if (!Q || !K || !V || !O) return FLAT_ERR_NULL;
     if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0) return FLAT_ERR_SHAPE;
     if (!fused_bf16_head_dim(d)) return FLAT_ERR_UNSUPPORTED;
@@ -79,9 +65,71 @@ int flat_attn_fwd_cross(const void* Q, const void* K, const void* V, void* O, in
     const size_t qbytes = (size_t)qbytes128, kbytes = (size_t)kbytes128;
     if (overlaps(O, qbytes, Q, qbytes) || overlaps(O, qbytes, K, kbytes) || overlaps(O, qbytes, V, kbytes)) return FLAT_ERR_ALIAS;
     if (kv_lens && overlaps(O, qbytes, kv_lens, (size_t)B * sizeof(int))) return FLAT_ERR_ALIAS;
+    *qbytes_out = qbytes;
+    *kbytes_out = kbytes;
+    return FLAT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int flat_attn_fwd(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
+                  int mask_kind, void* stream) {
+    const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 2, true);
+    if (rc != FLAT_OK) return rc;
+    if ((unsigned long long)N * (unsigned)d * 2u > 0xffffffffULL) return FLAT_ERR_SHAPE;  // the kernel addresses one head with 32-bit byte offsets
+    const flat::Bf16Problem prob{N, N, 0, H, nullptr, nullptr, nullptr, 0};
+    const hipError_t e = flat::launch_fwd_bf16(Q, K, V, O, B * H, prob, d, scale, mask_kind == FLAT_MASK_CAUSAL,
+                                               static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
+}
+
+int flat_attn_fwd_cross(const void* Q, const void* K, const void* V, void* O, int B, int H, int Nq, int Nk, int d, float scale,
+                        int mask_kind, const int* kv_lens, void* stream) {
+    size_t qbytes = 0, kbytes = 0;
+    const int rc = check_cross(Q, K, V, O, B, H, Nq, Nk, d, scale, mask_kind, kv_lens, &qbytes, &kbytes);
+    if (rc != FLAT_OK) return rc;
     const flat::Bf16Problem prob{Nq, Nk, mask_kind == FLAT_MASK_CAUSAL ? Nk - Nq : 0, H, kv_lens, nullptr, nullptr, 0};
     const hipError_t e = flat::launch_fwd_bf16(Q, K, V, O, B * H, prob, d, scale, mask_kind == FLAT_MASK_CAUSAL,
                                                static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
+}
+
+int flat_attn_fwd_splitkv_splits(int B, int H, int Nq, int Nk, int d, int n_splits) {
+    if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || (long long)B * H > 0x7fffffffLL) return FLAT_ERR_SHAPE;
+    if (!fused_bf16_head_dim(d)) return FLAT_ERR_UNSUPPORTED;
+    flat::SplitPlan plan;
+    if (!flat::split_plan(B * H, Nq, Nk, d, n_splits, &plan)) return FLAT_ERR_SHAPE;
+    return plan.n_splits;
+}
+
+size_t flat_attn_fwd_splitkv_workspace_bytes(int B, int H, int Nq, int Nk, int d, int n_splits) {
+    if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || (long long)B * H > 0x7fffffffLL || !fused_bf16_head_dim(d)) return 0;
+    flat::SplitPlan plan;
+    return flat::split_plan(B * H, Nq, Nk, d, n_splits, &plan) ? plan.workspace_bytes : 0;
+}
+
+int flat_attn_fwd_splitkv(const void* Q, const void* K, const void* V, void* O, int B, int H, int Nq, int Nk, int d, float scale,
+                          int mask_kind, const int* kv_lens, int n_splits, void* workspace, size_t workspace_bytes, void* stream) {
+    size_t qbytes = 0, kbytes = 0;
+    const int rc = check_cross(Q, K, V, O, B, H, Nq, Nk, d, scale, mask_kind, kv_lens, &qbytes, &kbytes);
+    if (rc != FLAT_OK) return rc;
+    if (!workspace) return FLAT_ERR_NULL;
+    if (!aligned16(workspace)) return FLAT_ERR_ALIGN;
+    flat::SplitPlan plan;
+    if (!flat::split_plan(B * H, Nq, Nk, d, n_splits, &plan)) return FLAT_ERR_SHAPE;
+    if (workspace_bytes < plan.workspace_bytes) return FLAT_ERR_WORKSPACE;
+    if (overlaps(workspace, plan.workspace_bytes, Q, qbytes) || overlaps(workspace, plan.workspace_bytes, K, kbytes) ||
+        overlaps(workspace, plan.workspace_bytes, V, kbytes) || overlaps(workspace, plan.workspace_bytes, O, qbytes))
+        return FLAT_ERR_ALIAS;
+    if (kv_lens && overlaps(workspace, plan.workspace_bytes, kv_lens, (size_t)B * sizeof(int))) return FLAT_ERR_ALIAS;
+    flat::Bf16Problem prob{Nq, Nk, mask_kind == FLAT_MASK_CAUSAL ? Nk - Nq : 0, H, kv_lens, nullptr, nullptr, 0};
+    prob.n_splits = plan.n_splits;
+    prob.tiles_per_split = plan.tiles_per_split;
+    prob.split_ws = static_cast<float*>(workspace);
+    const hipError_t e = flat::launch_fwd_bf16_split(Q, K, V, O, B * H, prob, d, scale, mask_kind == FLAT_MASK_CAUSAL,
+                                                     static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
 }
 

@@ -99,17 +99,22 @@ __device__ __forceinline__ void wait_vm() {
 constexpr int kMaxSparseTiles = 2048;  // block-sparse: listed tiles per row block that fit the LDS copy of the list (8 KiB)
 
 // Template parameters: D head dimension (32, 64, 96, 128, 256), QB 32-row blocks per wavefront, NW wavefronts per workgroup, STAGES
-// depth of the K/V ring, CAUSAL mask, SPARSE block-sparse variant (the workgroup visits only the 64-key tiles
+// depth of the K/V ring, CAUSAL mask, MODE: kDense, kSparse = block-sparse variant (the workgroup visits only the 64-key tiles
 // listed for its row block, ids ascending, staged in LDS behind the ring; everything else as in the dense kernel).
 // Two wavefronts per SIMD (256 registers each), except 64 rows per wavefront at d = 128 and every shape at d = 256,
 // whose accumulators alone need more: those run one wavefront per SIMD with the full 512 registers.
 
-template <int D, int QB, int NW, int STAGES, bool CAUSAL, bool SPARSE = false>
+// kSplit = the keys of one row block are divided over prob.n_splits workgroups, each of which leaves its
+// unnormalised result (reference maximum, row sum, accumulators) in a workspace for split_merge_kernel.
+constexpr int kDense = 0, kSparse = 1, kSplit = 2;
+
+template <int D, int QB, int NW, int STAGES, bool CAUSAL, int MODE = kDense>
 __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 2) void fwd_bf16_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                           const bf16* __restrict__ V, bf16* __restrict__ O,
                                                           const Bf16Problem prob, int n_qtiles, int n_blocks,
                                                           int blocks_per_xcd, float c) {
     using C = Bf16Cfg<D, STAGES, NW>;
+    constexpr bool SPARSE = MODE == kSparse, SPLIT = MODE == kSplit;
     constexpr int DP = C::DP, QW = 32 * QB, BR = NW * QW, BC = C::BC, DS = DP / 16, DB = DP / 32;
     constexpr int KB = BC / 32;    // 32-key blocks per tile
     constexpr int KB64 = 64 / BC;  // tiles per 64 keys (the unit of a block-sparse list)
@@ -149,6 +154,11 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
         qt = n_qtiles - 1 - from_end;
     }
 
+    int split = 0;
+    if (SPLIT) {  // the launch counts (row block, split) pairs per head; the splits of a row block are neighbours
+        split = qt % prob.n_splits;
+        qt /= prob.n_splits;
+    }
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     // Nq query rows per head; N = number of keys of this head that count (the padded tail of a shorter batch
     // entry is masked like the tail of a ragged tile); causal: query i sees keys 0 .. i + off.
@@ -188,8 +198,13 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
         for (int i = tid; i < sp_count; i += 64 * NW) sp_ids[i] = max(0, min(n_ktiles - 1, prob.tile_ids[lo + i]));
         __syncthreads();
     }
+    // Split keys: this workgroup takes tiles [t0, t0 + tiles_per_split) of those its row block sees.
+    int kv_len = N;
+    if (CAUSAL) kv_len = min(N, qt * BR + BR + off);
+    const int t0 = SPLIT ? split * prob.tiles_per_split : 0;
     // j-th tile this workgroup visits (a listed 64-key tile is KB64 consecutive tiles)
     auto tile_of = [&](int j) __attribute__((always_inline)) {
+        if (SPLIT) return t0 + j;
         if (!SPARSE) return j;
         return KB64 == 1 ? sp_ids[j] : sp_ids[j / KB64] * KB64 + j % KB64;
     };
@@ -199,7 +214,7 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
     float m[QB];
     {
         float k0[DS][8];
-        const int first_key = (SPARSE && sp_count > 0) ? sp_ids[0] * 64 : 0;
+        const int first_key = SPLIT ? min(t0 * BC, N - 1) : (SPARSE && sp_count > 0) ? sp_ids[0] * 64 : 0;
 #pragma unroll
         for (int ds = 0; ds < DS; ++ds) {
             uint4v kv = {0, 0, 0, 0};
@@ -230,9 +245,9 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
             for (int r = 0; r < 16; ++r) oacc[qb][db][r] = 0.f;
     }
 
-    int kv_len = N;
-    if (CAUSAL) kv_len = min(N, qt * BR + BR + off);
-    const int n_tiles = SPARSE ? sp_count * KB64 : (kv_len + BC - 1) / BC;  // tiles this workgroup visits
+    const int n_tiles_seen = (kv_len + BC - 1) / BC;  // tiles the row block sees
+    const int n_tiles = SPARSE ? sp_count * KB64                                              // tiles this workgroup visits
+                        : SPLIT ? max(0, min(n_tiles_seen - t0, prob.tiles_per_split)) : n_tiles_seen;
 
     // ---- global -> LDS streaming.  Wave w issues load i of a tile for the 1024-byte LDS block
     // (NW i + w); lane l fills slot (l % CHUNKS) of row (l / CHUNKS) of that block, so it fetches
@@ -500,7 +515,7 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
     auto tile_steps = [&](int j, int sj, bool masked, bool odd) __attribute__((always_inline)) {  // sj = j % STAGES
         const int sn = sj + 1 == STAGES ? 0 : sj + 1;       // stage of tile j+1
         // first 32-key block of the tile, as a key position / 32 (only the masked form of a step looks at it)
-        const int kb0 = KB * ((SPARSE && masked) ? tile_of(j) : j);
+        const int kb0 = KB * (((SPARSE && masked) || SPLIT) ? tile_of(j) : j);
         if (KB == 2) {
             if (kTwoVSets)
                 step(kb0, sj, sj, masked, xA, xB, pB, vfB, pA, vfA);
@@ -532,9 +547,11 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
     // streaming and synchronising for the others).
     const int n_vis_blocks = (N + 31) / 32;
     // (block-sparse: the list is ascending, so only its last 64 keys can hold the ragged end of the sequence)
-    const int n_unm_tiles = SPARSE ? max(n_tiles - KB64, 0) : (CAUSAL ? min((q0w + off + 1) / 32, N / 32) : N / 32) / KB;
-    const int n_act_tiles =
-        SPARSE ? n_tiles : ((CAUSAL ? min(n_vis_blocks, (q0w + QW - 1 + off) / 32 + 1) : n_vis_blocks) + KB - 1) / KB;
+    // (split keys: the same ranges, counted from the first tile of the split and cut to its length)
+    const int n_unm_all = (CAUSAL ? min((q0w + off + 1) / 32, N / 32) : N / 32) / KB;
+    const int n_act_all = ((CAUSAL ? min(n_vis_blocks, (q0w + QW - 1 + off) / 32 + 1) : n_vis_blocks) + KB - 1) / KB;
+    const int n_unm_tiles = SPARSE ? max(n_tiles - KB64, 0) : max(0, min(n_unm_all - t0, n_tiles));
+    const int n_act_tiles = SPARSE ? n_tiles : max(0, min(n_act_all - t0, n_tiles));
     int j = 0;
     // main loop: STAGES fully visible tiles per trip, so that every ring stage index is a constant
 #pragma unroll 1
@@ -576,6 +593,29 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
         sj = sj + 1 == STAGES ? 0 : sj + 1;
     }
 
+    // ---- split keys: leave the unnormalised partial result in the workspace.  Per (head, row block, split):
+    // BR rows x DP accumulators, then BR reference maxima, then BR row sums, all fp32.
+    if (SPLIT) {
+        const int n_row_blocks = n_qtiles / prob.n_splits;  // per head
+        float* part = prob.split_ws + ((size_t)(bh * n_row_blocks + qt) * prob.n_splits + split) * (size_t)(BR * (DP + 2));
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float total = halves_sum(lsum[qb]);
+            const int r_wg = wave * QW + 32 * qb + l32;  // row within the row block
+            if (half == 0) {
+                part[BR * DP + r_wg] = m[qb];
+                part[BR * DP + BR + r_wg] = total;
+            }
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    floatx4 w4 = {oacc[qb][db][4 * rq], oacc[qb][db][4 * rq + 1], oacc[qb][db][4 * rq + 2], oacc[qb][db][4 * rq + 3]};
+                    *(floatx4*)(part + (size_t)r_wg * DP + 32 * db + 8 * rq + 4 * half) = w4;
+                }
+        }
+        return;
+    }
     // ---- epilogue: O = O_acc / l, rounded to bf16; a lane holds 4 consecutive head-dim elements per register quad
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -598,15 +638,16 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
     }
 }
 
-template <int D, int QB, int NW, int STAGES, bool CAUSAL, bool SPARSE = false>
+template <int D, int QB, int NW, int STAGES, bool CAUSAL, int MODE = kDense>
 inline hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, float scale,
                              hipStream_t stream) {
     constexpr int BR = 32 * QB * NW;
-    const int n_qtiles = (prob.Nq + BR - 1) / BR;
+    // split keys: the kernel sees (row block, split) pairs where the other modes see row blocks
+    const int n_qtiles = (prob.Nq + BR - 1) / BR * (MODE == kSplit ? prob.n_splits : 1);
     const int n_blocks = BH * n_qtiles;
     const int blocks_per_xcd = (n_blocks + 7) / 8;
-    auto kern = fwd_bf16_kernel<D, QB, NW, STAGES, CAUSAL, SPARSE>;
-    constexpr int lds = Bf16Cfg<D, STAGES, NW>::LDS_BYTES + (SPARSE ? kMaxSparseTiles * (int)sizeof(int) : 0);
+    auto kern = fwd_bf16_kernel<D, QB, NW, STAGES, CAUSAL, MODE>;
+    constexpr int lds = Bf16Cfg<D, STAGES, NW>::LDS_BYTES + (MODE == kSparse ? kMaxSparseTiles * (int)sizeof(int) : 0);
     static std::atomic<uint64_t> attr_done{0};  // one flag per kernel instantiation
     hipError_t e = allow_dynamic_lds((const void*)kern, lds, &attr_done);
     if (e != hipSuccess) return e;
@@ -638,7 +679,7 @@ hipError_t fwd_bf16_shape_occupancy(int* workgroups_per_cu) {
 template <int D, int QB, int NW, int STAGES>
 hipError_t launch_fwd_bf16_sparse_shape(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob,
                                         float scale, hipStream_t stream) {
-    return launch_cfg<D, QB, NW, STAGES, false, true>(Q, K, V, O, BH, prob, scale, stream);
+    return launch_cfg<D, QB, NW, STAGES, false, kSparse>(Q, K, V, O, BH, prob, scale, stream);
 }
 
 #define FLAT_INSTANTIATE_BF16_SHAPE(D, QB, NW, STAGES)                                                                      \

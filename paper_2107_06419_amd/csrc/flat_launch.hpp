@@ -33,6 +33,11 @@ struct Bf16Problem {
     const int* tile_offsets;  // device, B*H*ceil(Nq/256) + 1 ints
     const int* tile_ids;      // device, n_tile_ids ints
     int n_tile_ids;
+    // split-keys launches only (else 0 / null): the keys of a row block are divided over n_splits workgroups of
+    // tiles_per_split tiles each, which leave their partial results in split_ws
+    int n_splits;
+    int tiles_per_split;
+    float* split_ws;
 };
 
 hipError_t launch_fwd_bf16(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,
@@ -40,6 +45,22 @@ hipError_t launch_fwd_bf16(const void* Q, const void* K, const void* V, void* O,
 
 hipError_t launch_fwd_bf16_sparse(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,
                                   float scale, hipStream_t stream);
+
+// Split keys (flat_splitkv.hip): for few query rows over many keys, where one workgroup per row block leaves most
+// of the chip idle.  The geometry is fixed per head dimension; split_plan fills in what a launch needs.
+struct SplitPlan {
+    int rows_per_block;    // query rows per workgroup of the shape used
+    int keys_per_tile;
+    int padded_d;          // accumulator columns stored per row
+    int n_row_blocks;      // per head
+    int n_tiles;           // key tiles per head
+    int n_splits;          // after clamping to [1, n_tiles]
+    int tiles_per_split;
+    size_t workspace_bytes;
+};
+bool split_plan(int BH, int Nq, int Nk, int d, int n_splits_wanted, SplitPlan* out);  // n_splits_wanted <= 0: chosen here
+hipError_t launch_fwd_bf16_split(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,
+                                 float scale, int causal, hipStream_t stream);
 
 // Tile shapes of the fused bf16 kernel (flat_tiles.hip).  Index 0 is the default of launch_fwd_bf16.
 struct TileShape {

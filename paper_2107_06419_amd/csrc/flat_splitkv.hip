@@ -1,0 +1,74 @@
+// Split-keys form of the fused bf16 kernel, for few query rows over many keys (a segment of new positions
+// attending over a long cache).  The row granularity of the paper's section 5.3 trades on-chip memory against how
+// well the compute array is filled; with a handful of row blocks the array stays empty whatever the tile size, so
+// here the key loop of a row block is divided over several workgroups, each leaving (reference maximum, row sum,
+// unnormalised output) in a workspace, and a second small kernel merges them.
+#include "flat_fwd_bf16_kernel.hpp"
+
+namespace flat {
+
+// Second pass of a split-keys launch: one thread per (head, query row, four output columns) merges the partial
+// results of the splits.  With m_s, l_s, O_s the reference maximum (log2 units), row sum and accumulators of
+// split s:  M = max m_s over the splits that saw a key,  O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+__global__ __launch_bounds__(256) void split_merge_kernel(const float* __restrict__ ws, bf16* __restrict__ O, int BH, int Nq,
+                                                          int n_row_blocks, int rows_per_block, int dp, int d, int n_splits) {
+    const int quads = d / 4;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)BH * Nq * quads) return;
+    const int quad = (int)(idx % quads);
+    const long long hr = idx / quads;
+    const int row = (int)(hr % Nq), bh = (int)(hr / Nq);
+    const int rb = row / rows_per_block, r = row - rb * rows_per_block;
+    const size_t stride = (size_t)rows_per_block * (dp + 2);
+    const float* base = ws + (size_t)(bh * n_row_blocks + rb) * n_splits * stride;
+    float M = -INFINITY;
+    for (int s = 0; s < n_splits; ++s) {
+        const float* part = base + s * stride + (size_t)rows_per_block * dp;
+        if (part[rows_per_block + r] > 0.f) M = __builtin_fmaxf(M, part[r]);
+    }
+    float L = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < n_splits; ++s) {
+        const float* part = base + s * stride;
+        const float l = part[(size_t)rows_per_block * dp + rows_per_block + r];
+        if (!(l > 0.f)) continue;  // a split whose keys this row does not see
+        const float w = __builtin_amdgcn_exp2f(part[(size_t)rows_per_block * dp + r] - M);
+        L += w * l;
+        const floatx4 o = *(const floatx4*)(part + (size_t)r * dp + 4 * quad);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += w * o[e];
+    }
+    const float inv = L > 0.f ? 1.0f / L : 0.f;
+    floatx2 out;
+    out[0] = __builtin_bit_cast(float, pack_bf16(acc[0] * inv, acc[1] * inv));
+    out[1] = __builtin_bit_cast(float, pack_bf16(acc[2] * inv, acc[3] * inv));
+    *(floatx2*)(O + ((size_t)bh * Nq + row) * d + 4 * quad) = out;
+}
+
+// Split-keys launch of one tile shape: the partial pass, then the merge.  prob carries n_splits, tiles_per_split
+// and the workspace (BH * ceil(Nq / BR) * n_splits * BR * (DP + 2) floats).
+template <int D, int QB, int NW, int STAGES>
+hipError_t launch_fwd_bf16_split_shape(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob,
+                                       float scale, int causal, hipStream_t stream) {
+    constexpr int BR = 32 * QB * NW;
+    const hipError_t e = causal ? launch_cfg<D, QB, NW, STAGES, true, kSplit>(Q, K, V, O, BH, prob, scale, stream)
+                                : launch_cfg<D, QB, NW, STAGES, false, kSplit>(Q, K, V, O, BH, prob, scale, stream);
+    if (e != hipSuccess) return e;
+    const long long threads = (long long)BH * prob.Nq * (D / 4);
+    hipLaunchKernelGGL(split_merge_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, prob.split_ws, (bf16*)O,
+                       BH, prob.Nq, (prob.Nq + BR - 1) / BR, BR, Bf16Cfg<D, STAGES, NW>::DP, D, prob.n_splits);
+    return hipGetLastError();
+}
+
+hipError_t launch_fwd_bf16_split(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,
+                                 float scale, int causal, hipStream_t stream) {
+    switch (d) {
+        case 32: return launch_fwd_bf16_split_shape<32, 2, 4, 4>(Q, K, V, O, BH, prob, scale, causal, stream);
+        case 64: return launch_fwd_bf16_split_shape<64, 2, 4, 4>(Q, K, V, O, BH, prob, scale, causal, stream);
+        case 96: return launch_fwd_bf16_split_shape<96, 1, 8, 3>(Q, K, V, O, BH, prob, scale, causal, stream);
+        case 128: return launch_fwd_bf16_split_shape<128, 1, 8, 3>(Q, K, V, O, BH, prob, scale, causal, stream);
+        case 256: return launch_fwd_bf16_split_shape<256, 1, 4, 4>(Q, K, V, O, BH, prob, scale, causal, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace flat

@@ -1,6 +1,6 @@
 // Host-only check run under AddressSanitizer and UndefinedBehaviorSanitizer (tests/test_sanitizers_host.py
 // builds and runs it; no GPU, no HIP runtime).  It links
-//   * the argument-validation half of the C ABI (csrc/flat_api.hip compiled as plain C++) against stub
+//   * the argument-validation half of the C ABI (csrc/flat_api.hip and csrc/flat_plan.hip compiled as plain C++) against stub
 //     launchers that only count calls, and walks its error paths with pointers that are never dereferenced;
 //   * the CPU oracle, and runs every entry point of it on small problems with row subsets, key counts, block
 //     patterns and several threads, comparing with a direct long-double evaluation.
@@ -21,6 +21,10 @@ static int g_launches = 0;
 namespace flat {
 hipError_t launch_fwd_bf16(const void*, const void*, const void*, void*, int, const Bf16Problem&, int, float, int, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_fwd_bf16_sparse(const void*, const void*, const void*, void*, int, const Bf16Problem&, int, float, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_fwd_bf16_split(const void*, const void*, const void*, void*, int, const Bf16Problem& p, int, float, int, hipStream_t) {
+    ++g_launches;
+    return (p.n_splits >= 1 && p.tiles_per_split >= 1 && p.split_ws) ? hipSuccess : hipErrorInvalidValue;
+}
 hipError_t launch_fwd_bf16_tile(const void*, const void*, const void*, void*, int, const Bf16Problem&, int, float, int, int, hipStream_t) { ++g_launches; return hipSuccess; }
 int tile_shape_count(int d) { return (d == 64 || d == 128) ? 2 : (d == 32 || d == 96 || d == 256) ? 1 : 0; }
 bool tile_shape(int d, int index, TileShape* out) {
@@ -85,6 +89,28 @@ static void check_validation() {
     EXPECT(flat_attn_fwd_cross(Q, K, V, O, 1, 1, 16, 16, 64, 1.f, 0, reinterpret_cast<const int*>(fake(0x7000002)), nullptr) == FLAT_ERR_ALIGN);
     EXPECT(flat_attn_fwd_cross(Q, K, V, O, 2, 2, 16, 900, 96, 1.f, 1, lens_storage, nullptr) == FLAT_OK);
     EXPECT(flat_attn_fwd_cross(Q, K, V, O, 1, 1, 2147483647, 2147483647, 256, 1.f, 0, nullptr, nullptr) == FLAT_ERR_SHAPE);
+
+    // split keys: the plan is real host code (csrc/flat_plan.hip), the launch is a stub
+    EXPECT(flat_attn_fwd_splitkv_splits(1, 16, 256, 65536, 64, 0) == 64);
+    EXPECT(flat_attn_fwd_splitkv_splits(1, 16, 256, 65536, 64, 7) == 7);
+    EXPECT(flat_attn_fwd_splitkv_splits(1, 1, 1, 100, 64, 9) == 2);          // two tiles: at most two splits
+    EXPECT(flat_attn_fwd_splitkv_splits(1, 1, 1, 100, 80, 0) == FLAT_ERR_UNSUPPORTED);
+    EXPECT(flat_attn_fwd_splitkv_splits(0, 1, 1, 100, 64, 0) == FLAT_ERR_SHAPE);
+    EXPECT(flat_attn_fwd_splitkv_splits(2147483647, 2147483647, 2147483647, 2147483647, 256, 0) == FLAT_ERR_SHAPE);
+    EXPECT(flat_attn_fwd_splitkv_workspace_bytes(1, 16, 256, 65536, 64, 8) == (size_t)16 * 8 * 256 * 66 * 4);
+    EXPECT(flat_attn_fwd_splitkv_workspace_bytes(1, 16, 300, 65536, 256, 8) == (size_t)16 * 3 * 8 * 128 * 258 * 4);
+    EXPECT(flat_attn_fwd_splitkv_workspace_bytes(1, 1, 2147483647, 2147483647, 256, 2147483647) == 0 ||
+           flat_attn_fwd_splitkv_workspace_bytes(1, 1, 2147483647, 2147483647, 256, 2147483647) > 0);  // no overflow trap either way
+    void* big_ws = fake(0x10000000);
+    const size_t need = flat_attn_fwd_splitkv_workspace_bytes(2, 2, 16, 900, 96, 4);
+    EXPECT(need > 0);
+    EXPECT(flat_attn_fwd_splitkv(Q, K, V, O, 2, 2, 16, 900, 96, 1.f, 1, lens_storage, 4, nullptr, need, nullptr) == FLAT_ERR_NULL);
+    EXPECT(flat_attn_fwd_splitkv(Q, K, V, O, 2, 2, 16, 900, 96, 1.f, 1, lens_storage, 4, big_ws, need - 1, nullptr) == FLAT_ERR_WORKSPACE);
+    EXPECT(flat_attn_fwd_splitkv(Q, K, V, O, 2, 2, 16, 900, 96, 1.f, 1, lens_storage, 4, fake(0x10000004), need, nullptr) == FLAT_ERR_ALIGN);
+    EXPECT(flat_attn_fwd_splitkv(Q, K, V, O, 2, 2, 16, 900, 96, 1.f, 1, lens_storage, 4, O, need, nullptr) == FLAT_ERR_ALIAS);
+    EXPECT(flat_attn_fwd_splitkv(Q, K, V, O, 2, 2, 17, 16, 96, 1.f, 1, lens_storage, 4, big_ws, need, nullptr) == FLAT_ERR_UNSUPPORTED);
+    EXPECT(flat_attn_fwd_splitkv(Q, K, V, O, 2, 2, 16, 900, 96, 1.f, 1, lens_storage, 4, big_ws, need, nullptr) == FLAT_OK);
+    EXPECT(flat_attn_fwd_splitkv(Q, K, V, O, 2, 2, 16, 900, 96, 1.f, 0, nullptr, 0, big_ws, need, nullptr) == FLAT_OK);
 
     EXPECT(flat_attn_fwd_f32((const float*)Q, (const float*)K, (const float*)V, (float*)O, 1, 1, 8, 32, 1.f, 0, nullptr) == FLAT_ERR_UNSUPPORTED);
     EXPECT(flat_attn_fwd_f32((const float*)Q, (const float*)K, (const float*)V, (float*)O, 1, 1, 8, 64, 1.f, 0, nullptr) == FLAT_OK);

@@ -109,6 +109,25 @@ int flat_attn_fwd_splitkv(const void* Q, const void* K, const void* V, void* O,
                           const int* kv_lens, int n_splits, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * flat_attn_fwd_splitkv for callers that cannot allocate device memory or hand over a workspace: code running under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  The partial results go to a scratch
+ * buffer of FLAT_SPLITKV_STATIC_BYTES that is part of the library's device image (every GPU the library runs on
+ * holds its own copy until the process ends); the call allocates and frees nothing.
+ *   Arguments and results as flat_attn_fwd_splitkv without workspace / workspace_bytes.
+ *   n_splits > 0 whose partial results need more than FLAT_SPLITKV_STATIC_BYTES: FLAT_ERR_WORKSPACE (use fewer
+ *     splits, or flat_attn_fwd_splitkv with a workspace of your own).  n_splits <= 0: the library's choice, reduced
+ *     to what the buffer holds; FLAT_ERR_WORKSPACE if not even one split fits (B*H*ceil(Nq/rows per block) too large).
+ *   With the same n_splits in effect the output is bit-identical to flat_attn_fwd_splitkv.
+ *   All calls on one GPU share the one buffer: calls that may overlap in time on the same GPU (different streams,
+ *   different threads) race and must be serialised by the caller.  Nothing in the buffer needs clearing between calls:
+ *   every launch overwrites all it later reads.
+ */
+#define FLAT_SPLITKV_STATIC_BYTES (64u << 20)
+int flat_attn_fwd_splitkv_static(const void* Q, const void* K, const void* V, void* O,
+                                 int B, int H, int Nq, int Nk, int d, float scale, int mask_kind,
+                                 const int* kv_lens, int n_splits, void* stream);
+
+/*
  * Block-sparse variant.  The paper asks (section 8.2, compatibility with sparse-attention accelerators) whether
  * the Logit/Attend pair stays worth fusing when the N x N matrix is pruned, and prunes it randomly at 50 %.  On
  * this hardware pruning pays only at about the granularity the kernel works at, so the pattern is given in blocks of

@@ -63,6 +63,8 @@ def load_library():
     lib.flat_attn_fwd_splitkv_workspace_bytes.argtypes = [i, i, i, i, i, i]
     lib.flat_attn_fwd_splitkv.restype = i
     lib.flat_attn_fwd_splitkv.argtypes = [vp, vp, vp, vp, i, i, i, i, i, f, i, vp, i, vp, sz, vp]
+    lib.flat_attn_fwd_splitkv_static.restype = i
+    lib.flat_attn_fwd_splitkv_static.argtypes = [vp, vp, vp, vp, i, i, i, i, i, f, i, vp, i, vp]
     lib.flat_attn_fwd_blocksparse.restype = i
     lib.flat_attn_fwd_blocksparse.argtypes = [vp, vp, vp, vp, i, i, i, i, f, vp, vp, i, vp]
     lib.flat_attn_fwd_f32.restype = i
@@ -195,6 +197,16 @@ def flat_attn_fwd_splitkv(Q, K, V, O, scale: float, mask_kind: int, kv_lens, n_s
     _check(load_library().flat_attn_fwd_splitkv(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, Nq, Nk, d,
                                                 float(scale), int(mask_kind), lens_ptr, int(n_splits), workspace.data_ptr(),
                                                 workspace.numel() * workspace.element_size(), _stream_handle(stream)))
+
+
+FLAT_SPLITKV_STATIC_BYTES = 64 << 20
+
+
+def flat_attn_fwd_splitkv_static(Q, K, V, O, scale: float, mask_kind: int, kv_lens=None, n_splits: int = 0, stream=None) -> None:
+    """flat_attn_fwd_splitkv out of the library's built-in scratch buffer (FLAT_SPLITKV_STATIC_BYTES): allocates nothing."""
+    B, H, Nq, Nk, d, lens_ptr = _cross_args(Q, K, V, O, kv_lens)
+    _check(load_library().flat_attn_fwd_splitkv_static(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, Nq, Nk, d,
+                                                       float(scale), int(mask_kind), lens_ptr, int(n_splits), _stream_handle(stream)))
 
 
 FLAT_SPARSE_BLOCK_ROWS = 256

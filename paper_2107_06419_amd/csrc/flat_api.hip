@@ -133,6 +133,29 @@ int flat_attn_fwd_splitkv(const void* Q, const void* K, const void* V, void* O, 
     return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
 }
 
+int flat_attn_fwd_splitkv_static(const void* Q, const void* K, const void* V, void* O, int B, int H, int Nq, int Nk, int d,
+                                 float scale, int mask_kind, const int* kv_lens, int n_splits, void* stream) {
+    size_t qbytes = 0, kbytes = 0;
+    const int rc = check_cross(Q, K, V, O, B, H, Nq, Nk, d, scale, mask_kind, kv_lens, &qbytes, &kbytes);
+    if (rc != FLAT_OK) return rc;
+    flat::SplitPlan plan;
+    if (!flat::split_plan(B * H, Nq, Nk, d, n_splits, &plan)) return FLAT_ERR_SHAPE;
+    if (plan.workspace_bytes > flat::kSplitStaticScratchBytes) {
+        if (n_splits > 0) return FLAT_ERR_WORKSPACE;  // the caller's choice does not fit the built-in scratch buffer
+        // the library's choice: as many splits as the buffer holds
+        const size_t per_split = plan.workspace_bytes / (size_t)plan.n_splits;
+        const size_t fit = flat::kSplitStaticScratchBytes / per_split;
+        if (fit < 1 || !flat::split_plan(B * H, Nq, Nk, d, (int)fit, &plan) || plan.workspace_bytes > flat::kSplitStaticScratchBytes)
+            return FLAT_ERR_WORKSPACE;
+    }
+    flat::Bf16Problem prob{Nq, Nk, mask_kind == FLAT_MASK_CAUSAL ? Nk - Nq : 0, H, kv_lens, nullptr, nullptr, 0};
+    prob.n_splits = plan.n_splits;
+    prob.tiles_per_split = plan.tiles_per_split;
+    const hipError_t e = flat::launch_fwd_bf16_split_static(Q, K, V, O, B * H, prob, d, scale, mask_kind == FLAT_MASK_CAUSAL,
+                                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
+}
+
 int flat_attn_fwd_f32(const float* Q, const float* K, const float* V, float* O, int B, int H, int N, int d, float scale,
                       int mask_kind, void* stream) {
     const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 4);

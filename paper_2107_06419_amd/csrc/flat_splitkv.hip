@@ -71,4 +71,34 @@ hipError_t launch_fwd_bf16_split(const void* Q, const void* K, const void* V, vo
     }
 }
 
+// ---- the same launch out of a scratch buffer that lives in the library's own device image ---------------------------------
+// For callers that must not allocate.  The array below is a host-side handle only: its device address differs per
+// GPU and is looked up once per device with hipGetSymbolAddress; kernels and launches only ever see that address.
+static __device__ __align__(256) float scratch[kSplitStaticScratchBytes / sizeof(float)];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<float*> g_scratch_addr[kMaxDevices];  // device address of `scratch` on each GPU, null until first use there
+}  // namespace
+
+hipError_t launch_fwd_bf16_split_static(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob,
+                                        int d, float scale, int causal, hipStream_t stream) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    float* addr = g_scratch_addr[dev].load(std::memory_order_acquire);
+    if (!addr) {
+        void* sym = nullptr;
+        e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));  // with `dev` current: every GPU has its own copy
+        if (e != hipSuccess) return e;
+        if (!sym) return hipErrorInvalidSymbol;
+        addr = static_cast<float*>(sym);
+        g_scratch_addr[dev].store(addr, std::memory_order_release);
+    }
+    Bf16Problem p = prob;
+    p.split_ws = addr;
+    return launch_fwd_bf16_split(Q, K, V, O, BH, p, d, scale, causal, stream);
+}
+
 }  // namespace flat

@@ -18,12 +18,18 @@
 
 // ---- stub launchers: the validation code must never get here with bad arguments --------------------------------------
 static int g_launches = 0;
+static int g_static_splits = 0;  // n_splits of the last allocation-free split-keys launch
 namespace flat {
 hipError_t launch_fwd_bf16(const void*, const void*, const void*, void*, int, const Bf16Problem&, int, float, int, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_fwd_bf16_sparse(const void*, const void*, const void*, void*, int, const Bf16Problem&, int, float, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_fwd_bf16_split(const void*, const void*, const void*, void*, int, const Bf16Problem& p, int, float, int, hipStream_t) {
     ++g_launches;
     return (p.n_splits >= 1 && p.tiles_per_split >= 1 && p.split_ws) ? hipSuccess : hipErrorInvalidValue;
+}
+hipError_t launch_fwd_bf16_split_static(const void*, const void*, const void*, void*, int, const Bf16Problem& p, int, float, int, hipStream_t) {
+    ++g_launches;
+    g_static_splits = p.n_splits;
+    return (p.n_splits >= 1 && p.tiles_per_split >= 1) ? hipSuccess : hipErrorInvalidValue;
 }
 hipError_t launch_fwd_bf16_tile(const void*, const void*, const void*, void*, int, const Bf16Problem&, int, float, int, int, hipStream_t) { ++g_launches; return hipSuccess; }
 int tile_shape_count(int d) { return (d == 64 || d == 128) ? 2 : (d == 32 || d == 96 || d == 256) ? 1 : 0; }
@@ -111,6 +117,14 @@ static void check_validation() {
     EXPECT(flat_attn_fwd_splitkv(Q, K, V, O, 2, 2, 17, 16, 96, 1.f, 1, lens_storage, 4, big_ws, need, nullptr) == FLAT_ERR_UNSUPPORTED);
     EXPECT(flat_attn_fwd_splitkv(Q, K, V, O, 2, 2, 16, 900, 96, 1.f, 1, lens_storage, 4, big_ws, need, nullptr) == FLAT_OK);
     EXPECT(flat_attn_fwd_splitkv(Q, K, V, O, 2, 2, 16, 900, 96, 1.f, 0, nullptr, 0, big_ws, need, nullptr) == FLAT_OK);
+
+    // the allocation-free form: the plan must fit the built-in buffer
+    EXPECT(flat_attn_fwd_splitkv_static(Q, K, V, O, 2, 2, 16, 900, 96, 1.f, 1, lens_storage, 4, nullptr) == FLAT_OK && g_static_splits == 4);
+    EXPECT(flat_attn_fwd_splitkv_static(Q, fake(1ull << 40), fake(2ull << 40), O, 1, 16, 256, 65536, 64, 1.f, 1, nullptr, 0, nullptr) == FLAT_OK);
+    EXPECT(g_static_splits >= 1 && (size_t)16 * g_static_splits * 256 * 66 * 4 <= FLAT_SPLITKV_STATIC_BYTES);
+    EXPECT(flat_attn_fwd_splitkv_static(Q, fake(1ull << 40), fake(2ull << 40), O, 1, 16, 256, 65536, 64, 1.f, 1, nullptr, 64, nullptr) == FLAT_ERR_WORKSPACE);
+    EXPECT(flat_attn_fwd_splitkv_static(Q, fake(1ull << 40), fake(2ull << 40), fake(3ull << 40), 64, 64, 256, 4096, 256, 1.f, 0, nullptr, 0, nullptr) == FLAT_ERR_WORKSPACE);
+    EXPECT(flat_attn_fwd_splitkv_static(nullptr, K, V, O, 2, 2, 16, 900, 96, 1.f, 1, lens_storage, 4, nullptr) == FLAT_ERR_NULL);
 
     EXPECT(flat_attn_fwd_f32((const float*)Q, (const float*)K, (const float*)V, (float*)O, 1, 1, 8, 32, 1.f, 0, nullptr) == FLAT_ERR_UNSUPPORTED);
     EXPECT(flat_attn_fwd_f32((const float*)Q, (const float*)K, (const float*)V, (float*)O, 1, 1, 8, 64, 1.f, 0, nullptr) == FLAT_OK);

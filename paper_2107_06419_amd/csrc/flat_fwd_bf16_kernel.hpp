@@ -602,6 +602,7 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
         for (int qb = 0; qb < QB; ++qb) {
             const float total = halves_sum(lsum[qb]);
             const int r_wg = wave * QW + 32 * qb + l32;  // row within the row block
+            if (qt * BR + r_wg >= Nq) continue;          // rows past the end are never merged
             if (half == 0) {
                 part[BR * DP + r_wg] = m[qb];
                 part[BR * DP + BR + r_wg] = total;

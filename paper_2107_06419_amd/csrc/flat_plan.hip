@@ -43,6 +43,7 @@ bool split_plan(int BH, int Nq, int Nk, int d, int n_splits_wanted, SplitPlan* o
     p.n_splits = (p.n_tiles + p.tiles_per_split - 1) / p.tiles_per_split;  // no split is left without a tile
     const unsigned __int128 bytes = (unsigned __int128)BH * p.n_row_blocks * p.n_splits * g.rows * (g.dp + 2) * sizeof(float);
     if (bytes >= ((unsigned __int128)1 << 62) || (long long)BH * p.n_row_blocks * p.n_splits > 0x7fffffffLL) return false;
+    if ((long long)BH * Nq > 0x7fffffffLL) return false;  // the merge launches one workgroup per (head, row)
     p.workspace_bytes = (size_t)bytes;
     *out = p;
     return true;

@@ -7,35 +7,54 @@
 
 namespace flat {
 
-// Second pass of a split-keys launch: one thread per (head, query row, four output columns) merges the partial
-// results of the splits.  With m_s, l_s, O_s the reference maximum (log2 units), row sum and accumulators of
-// split s:  M = max m_s over the splits that saw a key,  O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
-__global__ __launch_bounds__(256) void split_merge_kernel(const float* __restrict__ ws, bf16* __restrict__ O, int BH, int Nq,
-                                                          int n_row_blocks, int rows_per_block, int dp, int d, int n_splits) {
-    const int quads = d / 4;
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long long)BH * Nq * quads) return;
-    const int quad = (int)(idx % quads);
-    const long long hr = idx / quads;
-    const int row = (int)(hr % Nq), bh = (int)(hr / Nq);
+// Second pass of a split-keys launch: one workgroup per (head, query row) merges the partial results of the splits.
+// With m_s, l_s, O_s the reference maximum (log2 units), row sum and accumulators of split s:
+//     M = max m_s over the splits that saw a key,   O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// Thread t handles output columns 4 (t % quads) .. +3 and the splits t / quads, t / quads + lanes, ...; the lanes'
+// partial maxima and sums meet in LDS.  Sums are taken in a fixed order, so the result is reproducible.
+constexpr int kMergeThreads = 256;
+__global__ __launch_bounds__(kMergeThreads) void split_merge_kernel(const float* __restrict__ ws, bf16* __restrict__ O, int Nq,
+                                                                    int n_row_blocks, int rows_per_block, int dp, int d,
+                                                                    int n_splits) {
+    __shared__ float red[5][kMergeThreads];
+    const int quads = d / 4;                        // 8 .. 64
+    const int lanes = kMergeThreads / quads;        // split lanes (d = 96: 10, and the last 16 threads only meet the barriers)
+    const int tid = threadIdx.x, quad = tid % quads, lane = tid / quads;
+    const int first = lane < lanes ? lane : n_splits;  // first split of this thread
+    const int row = blockIdx.x % Nq, bh = blockIdx.x / Nq;
     const int rb = row / rows_per_block, r = row - rb * rows_per_block;
     const size_t stride = (size_t)rows_per_block * (dp + 2);
     const float* base = ws + (size_t)(bh * n_row_blocks + rb) * n_splits * stride;
+    const size_t m_at = (size_t)rows_per_block * dp + r, l_at = m_at + rows_per_block;
+
     float M = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) {
-        const float* part = base + s * stride + (size_t)rows_per_block * dp;
-        if (part[rows_per_block + r] > 0.f) M = __builtin_fmaxf(M, part[r]);
-    }
+    for (int s = first; s < n_splits; s += lanes)
+        if (base[s * stride + l_at] > 0.f) M = __builtin_fmaxf(M, base[s * stride + m_at]);
+    red[0][tid] = M;
+    __syncthreads();
+    for (int k = 0; k < lanes; ++k) M = __builtin_fmaxf(M, red[0][k * quads + quad]);
+    __syncthreads();
+
     float L = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < n_splits; ++s) {
+    for (int s = first; s < n_splits; s += lanes) {
         const float* part = base + s * stride;
-        const float l = part[(size_t)rows_per_block * dp + rows_per_block + r];
+        const float l = part[l_at];
         if (!(l > 0.f)) continue;  // a split whose keys this row does not see
-        const float w = __builtin_amdgcn_exp2f(part[(size_t)rows_per_block * dp + r] - M);
+        const float w = __builtin_amdgcn_exp2f(part[m_at] - M);
         L += w * l;
         const floatx4 o = *(const floatx4*)(part + (size_t)r * dp + 4 * quad);
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[e] += w * o[e];
+    }
+    red[0][tid] = L;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[1 + e][tid] = acc[e];
+    __syncthreads();
+    if (lane != 0) return;
+    for (int k = 1; k < lanes; ++k) {
+        L += red[0][k * quads + quad];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += red[1 + e][k * quads + quad];
     }
     const float inv = L > 0.f ? 1.0f / L : 0.f;
     floatx2 out;
@@ -53,9 +72,8 @@ hipError_t launch_fwd_bf16_split_shape(const void* Q, const void* K, const void*
     const hipError_t e = causal ? launch_cfg<D, QB, NW, STAGES, true, kSplit>(Q, K, V, O, BH, prob, scale, stream)
                                 : launch_cfg<D, QB, NW, STAGES, false, kSplit>(Q, K, V, O, BH, prob, scale, stream);
     if (e != hipSuccess) return e;
-    const long long threads = (long long)BH * prob.Nq * (D / 4);
-    hipLaunchKernelGGL(split_merge_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, prob.split_ws, (bf16*)O,
-                       BH, prob.Nq, (prob.Nq + BR - 1) / BR, BR, Bf16Cfg<D, STAGES, NW>::DP, D, prob.n_splits);
+    hipLaunchKernelGGL(split_merge_kernel, dim3((unsigned)BH * (unsigned)prob.Nq), dim3(kMergeThreads), 0, stream, prob.split_ws,
+                       (bf16*)O, prob.Nq, (prob.Nq + BR - 1) / BR, BR, Bf16Cfg<D, STAGES, NW>::DP, D, prob.n_splits);
     return hipGetLastError();
 }
 

@@ -15,6 +15,8 @@ def main() -> int:
     ap.add_argument("--reps", type=int, default=3)
     ap.add_argument("--unfused", action="store_true")
     ap.add_argument("--copy-mib", type=int, default=1024, help="size of the calibration copy (MiB read + MiB written)")
+    ap.add_argument("--cache", default="", help="H,Nq,Nk,d: instead of the above, a causal segment of Nq queries over Nk cached keys "
+                                                "through flat_attn_fwd_cross and flat_attn_fwd_splitkv")
     args = ap.parse_args()
 
     import numpy as np
@@ -23,6 +25,22 @@ def main() -> int:
     import paper_2107_06419_amd as fa
     from paper_2107_06419_amd import synth
 
+    if args.cache:
+        H, Nq, Nk, d = (int(t) for t in args.cache.split(","))
+        scale = float(np.float32(d ** -0.5))
+        tq = torch.randn(1, H, Nq, d, device="cuda").to(torch.bfloat16)
+        tk = torch.randn(1, H, Nk, d, device="cuda").to(torch.bfloat16)
+        tv = torch.randn(1, H, Nk, d, device="cuda").to(torch.bfloat16)
+        to = torch.empty_like(tq)
+        ws = torch.empty(fa.flat_attn_fwd_splitkv_workspace_bytes(1, H, Nq, Nk, d, 0) // 4, dtype=torch.float32, device="cuda")
+        for _ in range(args.reps):
+            fa.flat_attn_fwd_cross(tq, tk, tv, to, scale, 1)
+        torch.cuda.synchronize()
+        for _ in range(args.reps):
+            fa.flat_attn_fwd_splitkv(tq, tk, tv, to, scale, 1, None, 0, ws)
+        torch.cuda.synchronize()
+        print("profile_driver done cache", args.cache, "splits", fa.flat_attn_fwd_splitkv_splits(1, H, Nq, Nk, d, 0), flush=True)
+        return 0
     if args.shape:
         B, H, N, d, mask = (int(t) for t in args.shape.split(","))
         w = synth.custom("shape_" + args.shape.replace(",", "_"), B, H, N, d, "bf16", mask, seed=1)

@@ -418,12 +418,17 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
     // With d = 128 two sets of V fragments do not fit the register file next to the accumulators: then one
     // set is used, refilled in the middle of each step right after the MFMAs that consumed it were issued.
     constexpr bool kTwoVSets = (DP <= 64);
+    // d = 256 (one wavefront per SIMD, accumulators in the upper half of its 512 registers): the other half has to
+    // hold everything the vector ALU touches, so K fragments are kept 8 at a time and V fragments one 16-key half
+    // at a time, and the Attend of a block follows its softmax in the same step instead of being owed to the next.
+    constexpr bool kWide = (DP == 256);
+    constexpr int KFN = kWide ? DS / 2 : DS;
     // Pipeline state: xA/xB hold the logits of the current / next block, pA/pB and vfA/vfB the
     // probabilities and V fragments of the block whose Attend is still owed.
     floatx16 xA[QB], xB[QB];
     uint32_t pA[QB][8], pB[QB][8];
-    bf16x8 vfA[2][DB], vfB[2][DB];  // vfB stays unused with one set
-    bf16x8 kf[DS];
+    bf16x8 vfA[2][DB], vfB[2][DB];  // vfB stays unused with one set; the wide form uses vfA[0] only
+    bf16x8 kf[DS];                  // the wide form uses the first KFN
     float mx[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
@@ -433,8 +438,53 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
     for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int db = 0; db < DB; ++db) vfA[t][db] = vfB[t][db] = __builtin_bit_cast(bf16x8, (uint4v){0, 0, 0, 0});
-    read_k(0, 0, kf);
-    logits(kf, xA);
+    // wide form: K fragments ds = h KFN .. of one block, and the V fragments of one 16-key half t
+    auto read_k_half = [&](int stage, int kb, int h) __attribute__((always_inline)) {
+        typedef const bf16x8 __attribute__((address_space(3))) * lds_frag_ptr;
+        const int block_off = stage * C::STAGE + kb * 32 * C::ROWB;
+#pragma unroll
+        for (int i = 0; i < KFN; ++i) {
+            asm volatile("" : "+v"(koff[h * KFN + i]));
+            kf[i] = *(lds_frag_ptr)(uintptr_t)(uint32_t)(koff[h * KFN + i] + block_off);
+        }
+    };
+    auto read_v_half = [&](int stage, int kb, int t) __attribute__((always_inline)) {
+        const int off = stage * C::STAGE + C::KBYTES + kb * 32 * C::ROWB + t * 16 * C::ROWB;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            asm volatile("" : "+v"(voff[db][0]), "+v"(voff[db][1]));
+            vfA[0][db] = concat(lds_read_tr16_at(voff[db][0] + off), lds_read_tr16_at(voff[db][1] + off));
+        }
+    };
+    auto logits_half = [&](int h, floatx16 (&x)[QB]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < KFN; ++i)
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) x[qb] = mfma_bf16_32x32x16(kf[i], qf[qb][h * KFN + i], x[qb]);
+    };
+    auto attend_half = [&](int t, const uint32_t (&p)[QB][8]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                uint4v pw = {p[qb][4 * t], p[qb][4 * t + 1], p[qb][4 * t + 2], p[qb][4 * t + 3]};
+                oacc[qb][db] = mfma_bf16_32x32x16(vfA[0][db], __builtin_bit_cast(bf16x8, pw), oacc[qb][db]);
+            }
+    };
+    if (kWide) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) xA[qb][r] = 0.f;
+        read_k_half(0, 0, 0);
+        logits_half(0, xA);
+        __builtin_amdgcn_sched_barrier(0);
+        read_k_half(0, 0, 1);
+        logits_half(1, xA);
+    } else {
+        read_k(0, 0, kf);
+        logits(kf, xA);
+    }
 
     // One step = one block b:   matrix pipe: Attend(b-1) and S(b+1);   vector ALU: softmax(b).
     // Stage bookkeeping (tile j = blocks 2j, 2j+1; reads of step b touch K of block b+1 and V of block b):
@@ -442,6 +492,56 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
     //   before step 2j+1: start streaming tile j+STAGES-1 into the stage that held tile j-1
     auto step = [&](int blk, int stage, int next_stage, bool masked, floatx16 (&xc)[QB], floatx16 (&xn)[QB], const uint32_t (&pp)[QB][8],
                     const bf16x8 (&vp)[2][DB], uint32_t (&pc)[QB][8], bf16x8 (&vc)[2][DB]) __attribute__((always_inline)) {
+        if (kWide) {
+            // Wide head: S(b+1) in two halves with the softmax of block b spread under them, then Attend(b) in its
+            // two key halves; every batch of LDS reads has eight MFMAs (256 matrix-pipe cycles) ahead of its use.
+            constexpr auto kLgkm0 = (63 & 15) | ((63 >> 4) << 14) | (7 << 4) | (0 << 8);
+            float bs[QB];
+            read_k_half(next_stage, 0, 0);
+            read_v_half(stage, 0, 0);
+            if (kSyncEveryPhase) __builtin_amdgcn_s_waitcnt(kLgkm0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) xn[qb][r] = 0.f;
+            logits_half(0, xn);
+            shift(blk, masked, xc);
+#pragma unroll
+            for (int g = 0; g < QB * KFN; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, (QB * 16) / (QB * KFN), 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            read_k_half(next_stage, 0, 1);
+            if (kSyncEveryPhase) __builtin_amdgcn_s_waitcnt(kLgkm0);
+            __builtin_amdgcn_sched_barrier(0);
+            logits_half(1, xn);
+            softmax_b(xc, pc, bs);
+#pragma unroll
+            for (int g = 0; g < QB * KFN; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, (QB * 32) / (QB * KFN), 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            bool jumped = false;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) jumped |= !(bs[qb] <= kSumJump);
+            if (__builtin_amdgcn_ballot_w64(jumped) != 0) {  // exact path, before this block's Attend
+                row_max(xc, mx);
+                rescale(xc, mx);
+                softmax_b(xc, pc, bs);
+            }
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) lsum[qb] += bs[qb];
+            attend_half(0, pc);
+            __builtin_amdgcn_sched_barrier(0);
+            read_v_half(stage, 0, 1);
+            if (kSyncEveryPhase) __builtin_amdgcn_s_waitcnt(kLgkm0);
+            __builtin_amdgcn_sched_barrier(0);
+            attend_half(1, pc);
+            return;
+        }
         read_k(next_stage, (blk + 1) & (KB - 1), kf);
         if (kTwoVSets) read_v(stage, blk & (KB - 1), vc);
         if (kSyncEveryPhase) __builtin_amdgcn_s_waitcnt((63 & 15) | ((63 >> 4) << 14) | (7 << 4) | (0 << 8));  // lgkmcnt(0) only
@@ -583,10 +683,13 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
         if (j > n_act_tiles) j = n_act_tiles;
     }
     // the Attend still owed for the last block
-    if (owed_in_a)
-        attend(kTwoVSets ? vfA : vfA, pA);
-    else
+    if (kWide) {
+        // nothing is owed: every step ran its own Attend
+    } else if (owed_in_a) {
+        attend(vfA, pA);
+    } else {
         attend(kTwoVSets ? vfB : vfA, pB);
+    }
 #pragma unroll 1
     for (; j < n_tiles; ++j) {
         sync_and_stream(j, sj);

@@ -78,6 +78,7 @@ struct TileShape {
     int lds_bytes;           // dynamic LDS per workgroup
 };
 int tile_shape_count(int d);
+int default_tile_shape(int BH, int Nq, int d, int causal);  // index launch_fwd_bf16 uses for this problem
 bool tile_shape(int d, int index, TileShape* out);
 hipError_t tile_shape_occupancy(int d, int index, int* workgroups_per_cu);
 hipError_t launch_fwd_bf16_tile(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,

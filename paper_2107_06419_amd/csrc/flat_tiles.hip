@@ -77,9 +77,19 @@ hipError_t launch_fwd_bf16_tile(const void* Q, const void* K, const void* V, voi
     return e ? e->launch(Q, K, V, O, BH, prob, scale, causal, stream) : hipErrorInvalidValue;
 }
 
+// The shape flat_attn_fwd / flat_attn_fwd_cross run: index 0, except where the measured sweep (python -m
+// paper_2107_06419_amd.tile_sweep) shows another shape ahead by more than its run-to-run spread.  So far one rule:
+// d = 64 with the causal mask and enough row blocks to give every compute unit two 512-row workgroups in turn
+// takes the 8-wavefront, 512-row shape (index 3): half as many workgroups stream K and V, and their uneven
+// lengths (row block q needs q + 1 tiles) pack better (3 % at N = 16K; with fewer blocks the same shape loses 40 %).
+int default_tile_shape(int BH, int Nq, int d, int causal) {
+    if (d == 64 && causal && (long long)BH * (((long long)Nq + 511) / 512) >= 512) return 3;
+    return 0;
+}
+
 hipError_t launch_fwd_bf16(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,
                            float scale, int causal, hipStream_t stream) {
-    return launch_fwd_bf16_tile(Q, K, V, O, BH, prob, d, scale, causal, 0, stream);
+    return launch_fwd_bf16_tile(Q, K, V, O, BH, prob, d, scale, causal, default_tile_shape(BH, prob.Nq, d, causal), stream);
 }
 
 }  // namespace flat

@@ -17,6 +17,7 @@ def main() -> int:
     ap.add_argument("--copy-mib", type=int, default=1024, help="size of the calibration copy (MiB read + MiB written)")
     ap.add_argument("--cache", default="", help="H,Nq,Nk,d: instead of the above, a causal segment of Nq queries over Nk cached keys "
                                                 "through flat_attn_fwd_cross and flat_attn_fwd_splitkv")
+    ap.add_argument("--mix", action="store_true", help="instead of the above, the four levels of the instruction-mix probe")
     args = ap.parse_args()
 
     import numpy as np
@@ -25,6 +26,15 @@ def main() -> int:
     import paper_2107_06419_amd as fa
     from paper_2107_06419_amd import synth
 
+    if args.mix:
+        sink = torch.empty(fa.flat_attn_mix_probe_sink_bytes() // 4, dtype=torch.float32, device="cuda")
+        src = torch.randn(fa.flat_attn_mix_probe_src_bytes() // 2, device="cuda").to(torch.bfloat16)
+        for level in range(4):
+            for _ in range(args.reps):
+                fa.flat_attn_mix_probe(sink, src, level, 500)
+            torch.cuda.synchronize()
+        print("profile_driver done mix", flush=True)
+        return 0
     if args.cache:
         H, Nq, Nk, d = (int(t) for t in args.cache.split(","))
         scale = float(np.float32(d ** -0.5))

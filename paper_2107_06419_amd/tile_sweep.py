@@ -25,6 +25,12 @@ PROBLEMS = [
     ("wide 16K", 1, 8, 16384, 128, 0),
     ("wide short 1K", 8, 16, 1024, 128, 0),
     ("wide causal 32K", 1, 4, 32768, 128, 1),
+    ("narrow 16K", 1, 32, 16384, 32, 0),
+    ("narrow causal 8K", 2, 16, 8192, 32, 1),
+    ("d96 16K", 1, 12, 16384, 96, 0),
+    ("d96 causal 8K", 2, 8, 8192, 96, 1),
+    ("d256 16K", 1, 4, 16384, 256, 0),
+    ("d256 causal 8K", 2, 4, 8192, 256, 1),
 ]
 
 
@@ -66,7 +72,7 @@ def main() -> int:
         return torch.from_numpy(synth.f32_to_bf16_bits(x).reshape(x.shape).view(np.int16)).cuda().view(torch.bfloat16)
 
     lines = []
-    for d in (64, 128):
+    for d in (64, 128, 32, 96, 256):
         n = fa.flat_attn_tile_shape_count(d)
         shapes = [fa.flat_attn_tile_shape_get(d, i).as_dict() for i in range(n)]
         occ = [fa.flat_attn_tile_shape_occupancy(d, i) for i in range(n)]

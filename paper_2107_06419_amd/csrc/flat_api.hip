@@ -128,8 +128,8 @@ int flat_attn_fwd_splitkv(const void* Q, const void* K, const void* V, void* O, 
     prob.n_splits = plan.n_splits;
     prob.tiles_per_split = plan.tiles_per_split;
     prob.split_ws = static_cast<float*>(workspace);
-    const hipError_t e = flat::launch_fwd_bf16_split(Q, K, V, O, B * H, prob, d, scale, mask_kind == FLAT_MASK_CAUSAL,
-                                                     static_cast<hipStream_t>(stream));
+    const hipError_t e = flat::launch_fwd_bf16_split(Q, K, V, O, B * H, prob, d, plan.rows_per_block, scale,
+                                                     mask_kind == FLAT_MASK_CAUSAL, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
 }
 
@@ -151,8 +151,8 @@ int flat_attn_fwd_splitkv_static(const void* Q, const void* K, const void* V, vo
     flat::Bf16Problem prob{Nq, Nk, mask_kind == FLAT_MASK_CAUSAL ? Nk - Nq : 0, H, kv_lens, nullptr, nullptr, 0};
     prob.n_splits = plan.n_splits;
     prob.tiles_per_split = plan.tiles_per_split;
-    const hipError_t e = flat::launch_fwd_bf16_split_static(Q, K, V, O, B * H, prob, d, scale, mask_kind == FLAT_MASK_CAUSAL,
-                                                            static_cast<hipStream_t>(stream));
+    const hipError_t e = flat::launch_fwd_bf16_split_static(Q, K, V, O, B * H, prob, d, plan.rows_per_block, scale,
+                                                            mask_kind == FLAT_MASK_CAUSAL, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FLAT_OK : FLAT_ERR_HIP;
 }
 

@@ -60,12 +60,12 @@ struct SplitPlan {
 };
 bool split_plan(int BH, int Nq, int Nk, int d, int n_splits_wanted, SplitPlan* out);  // n_splits_wanted <= 0: chosen here
 hipError_t launch_fwd_bf16_split(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,
-                                 float scale, int causal, hipStream_t stream);
+                                 int rows_per_block, float scale, int causal, hipStream_t stream);
 // The same launch with the partial results in a scratch array inside the library's device image (prob.split_ws is
 // ignored): nothing is allocated.  The plan's workspace_bytes must not exceed kSplitStaticScratchBytes.
 constexpr size_t kSplitStaticScratchBytes = (size_t)64 << 20;
 hipError_t launch_fwd_bf16_split_static(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob,
-                                        int d, float scale, int causal, hipStream_t stream);
+                                        int d, int rows_per_block, float scale, int causal, hipStream_t stream);
 
 // Tile shapes of the fused bf16 kernel (flat_tiles.hip).  Index 0 is the default of launch_fwd_bf16.
 struct TileShape {

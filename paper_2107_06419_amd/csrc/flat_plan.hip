@@ -5,25 +5,35 @@
 namespace flat {
 
 namespace {
-// the default tile shape of every head dimension: rows per workgroup, keys per tile, padded head dimension
-struct Geometry { int rows, keys, dp; };
-bool geometry(int d, Geometry* g) {
+// The tile shape a split-keys launch uses: rows per workgroup, keys per tile, padded head dimension, workgroups that
+// fit a compute unit.  Every workgroup multiplies a full tile of `rows` rows whatever Nq is, so at d = 64 (where the
+// template has them: flat_splitkv.hip) few query rows take a shape with fewer rows.
+struct Geometry { int rows, keys, dp, per_cu; };
+bool geometry(int d, int Nq, Geometry* g) {
     switch (d) {
-        case 32: *g = {256, 64, 32}; return true;
-        case 64: *g = {256, 64, 64}; return true;
-        case 96: *g = {256, 64, 128}; return true;
-        case 128: *g = {256, 64, 128}; return true;
-        case 256: *g = {128, 32, 256}; return true;
+        case 32: *g = {256, 64, 32, 2}; return true;
+        case 64:
+            if (Nq <= 32) *g = {32, 64, 64, 3};
+            else if (Nq <= 64) *g = {64, 64, 64, 2};
+            else if (Nq <= 128) *g = {128, 64, 64, 2};
+            else *g = {256, 64, 64, 2};
+            return true;
+        case 96: *g = {256, 64, 128, 1}; return true;
+        case 128:
+            if (Nq <= 128) *g = {128, 64, 128, 1};
+            else *g = {256, 64, 128, 1};
+            return true;
+        case 256: *g = {128, 32, 256, 1}; return true;
         default: return false;
     }
 }
-constexpr int kWorkgroupSlots = 512;   // 256 compute units x 2 resident workgroups of the d = 64 shape
+constexpr int kComputeUnits = 256;
 constexpr int kMinTilesPerSplit = 8;   // below this the prologue and the merge outweigh the gain
 }  // namespace
 
 bool split_plan(int BH, int Nq, int Nk, int d, int n_splits_wanted, SplitPlan* out) {
     Geometry g;
-    if (!geometry(d, &g) || BH <= 0 || Nq <= 0 || Nk <= 0) return false;
+    if (BH <= 0 || Nq <= 0 || Nk <= 0 || !geometry(d, Nq, &g)) return false;
     SplitPlan p;
     p.rows_per_block = g.rows;
     p.keys_per_tile = g.keys;
@@ -33,7 +43,7 @@ bool split_plan(int BH, int Nq, int Nk, int d, int n_splits_wanted, SplitPlan* o
     long long s = n_splits_wanted;
     if (s <= 0) {  // fill the chip about twice over, but keep every split long enough to pay for itself
         const long long blocks = (long long)BH * p.n_row_blocks;
-        s = (2 * kWorkgroupSlots + blocks - 1) / blocks;
+        s = (2 * kComputeUnits * g.per_cu + blocks - 1) / blocks;
         const long long longest = (p.n_tiles + kMinTilesPerSplit - 1) / kMinTilesPerSplit;
         if (s > longest) s = longest;
     }

@@ -77,14 +77,19 @@ hipError_t launch_fwd_bf16_split_shape(const void* Q, const void* K, const void*
     return hipGetLastError();
 }
 
+// rows = rows per workgroup of the plan (split_plan): selects among the shapes built for a head dimension
 hipError_t launch_fwd_bf16_split(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,
-                                 float scale, int causal, hipStream_t stream) {
-    switch (d) {
-        case 32: return launch_fwd_bf16_split_shape<32, 2, 4, 4>(Q, K, V, O, BH, prob, scale, causal, stream);
-        case 64: return launch_fwd_bf16_split_shape<64, 2, 4, 4>(Q, K, V, O, BH, prob, scale, causal, stream);
-        case 96: return launch_fwd_bf16_split_shape<96, 1, 8, 3>(Q, K, V, O, BH, prob, scale, causal, stream);
-        case 128: return launch_fwd_bf16_split_shape<128, 1, 8, 3>(Q, K, V, O, BH, prob, scale, causal, stream);
-        case 256: return launch_fwd_bf16_split_shape<256, 1, 4, 4>(Q, K, V, O, BH, prob, scale, causal, stream);
+                                 int rows, float scale, int causal, hipStream_t stream) {
+    switch (d * 1000 + rows) {
+        case 32256: return launch_fwd_bf16_split_shape<32, 2, 4, 4>(Q, K, V, O, BH, prob, scale, causal, stream);
+        case 64032: return launch_fwd_bf16_split_shape<64, 1, 1, 3>(Q, K, V, O, BH, prob, scale, causal, stream);
+        case 64064: return launch_fwd_bf16_split_shape<64, 1, 2, 4>(Q, K, V, O, BH, prob, scale, causal, stream);
+        case 64128: return launch_fwd_bf16_split_shape<64, 1, 4, 4>(Q, K, V, O, BH, prob, scale, causal, stream);
+        case 64256: return launch_fwd_bf16_split_shape<64, 2, 4, 4>(Q, K, V, O, BH, prob, scale, causal, stream);
+        case 96256: return launch_fwd_bf16_split_shape<96, 1, 8, 3>(Q, K, V, O, BH, prob, scale, causal, stream);
+        case 128128: return launch_fwd_bf16_split_shape<128, 1, 4, 3>(Q, K, V, O, BH, prob, scale, causal, stream);
+        case 128256: return launch_fwd_bf16_split_shape<128, 1, 8, 3>(Q, K, V, O, BH, prob, scale, causal, stream);
+        case 256128: return launch_fwd_bf16_split_shape<256, 1, 4, 4>(Q, K, V, O, BH, prob, scale, causal, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -100,7 +105,7 @@ std::atomic<float*> g_scratch_addr[kMaxDevices];  // device address of `scratch`
 }  // namespace
 
 hipError_t launch_fwd_bf16_split_static(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob,
-                                        int d, float scale, int causal, hipStream_t stream) {
+                                        int d, int rows, float scale, int causal, hipStream_t stream) {
     int dev = -1;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
@@ -116,7 +121,7 @@ hipError_t launch_fwd_bf16_split_static(const void* Q, const void* K, const void
     }
     Bf16Problem p = prob;
     p.split_ws = addr;
-    return launch_fwd_bf16_split(Q, K, V, O, BH, p, d, scale, causal, stream);
+    return launch_fwd_bf16_split(Q, K, V, O, BH, p, d, rows, scale, causal, stream);
 }
 
 }  // namespace flat

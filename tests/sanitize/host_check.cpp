@@ -22,11 +22,11 @@ static int g_static_splits = 0;  // n_splits of the last allocation-free split-k
 namespace flat {
 hipError_t launch_fwd_bf16(const void*, const void*, const void*, void*, int, const Bf16Problem&, int, float, int, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_fwd_bf16_sparse(const void*, const void*, const void*, void*, int, const Bf16Problem&, int, float, hipStream_t) { ++g_launches; return hipSuccess; }
-hipError_t launch_fwd_bf16_split(const void*, const void*, const void*, void*, int, const Bf16Problem& p, int, float, int, hipStream_t) {
+hipError_t launch_fwd_bf16_split(const void*, const void*, const void*, void*, int, const Bf16Problem& p, int, int, float, int, hipStream_t) {
     ++g_launches;
     return (p.n_splits >= 1 && p.tiles_per_split >= 1 && p.split_ws) ? hipSuccess : hipErrorInvalidValue;
 }
-hipError_t launch_fwd_bf16_split_static(const void*, const void*, const void*, void*, int, const Bf16Problem& p, int, float, int, hipStream_t) {
+hipError_t launch_fwd_bf16_split_static(const void*, const void*, const void*, void*, int, const Bf16Problem& p, int, int, float, int, hipStream_t) {
     ++g_launches;
     g_static_splits = p.n_splits;
     return (p.n_splits >= 1 && p.tiles_per_split >= 1) ? hipSuccess : hipErrorInvalidValue;
@@ -100,6 +100,9 @@ static void check_validation() {
     EXPECT(flat_attn_fwd_splitkv_splits(1, 16, 256, 65536, 64, 0) == 64);
     EXPECT(flat_attn_fwd_splitkv_splits(1, 16, 256, 65536, 64, 7) == 7);
     EXPECT(flat_attn_fwd_splitkv_splits(1, 1, 1, 100, 64, 9) == 2);          // two tiles: at most two splits
+    EXPECT(flat_attn_fwd_splitkv_splits(1, 16, 1, 65536, 64, 0) == 94);      // 32-row shape, 3 workgroups per compute unit: 96 wanted,
+    EXPECT(flat_attn_fwd_splitkv_splits(1, 16, 1, 65536, 64, 96) == 94);     // 11 tiles each, and 94 such splits cover the 1024 tiles
+    EXPECT(flat_attn_fwd_splitkv_workspace_bytes(1, 16, 1, 65536, 64, 96) == (size_t)16 * 94 * 32 * 66 * 4);
     EXPECT(flat_attn_fwd_splitkv_splits(1, 1, 1, 100, 80, 0) == FLAT_ERR_UNSUPPORTED);
     EXPECT(flat_attn_fwd_splitkv_splits(0, 1, 1, 100, 64, 0) == FLAT_ERR_SHAPE);
     EXPECT(flat_attn_fwd_splitkv_splits(2147483647, 2147483647, 2147483647, 2147483647, 256, 0) == FLAT_ERR_SHAPE);

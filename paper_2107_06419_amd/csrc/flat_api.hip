@@ -290,9 +290,11 @@ const char* flat_attn_status_string(int status) {
             return "FLAT_ERR_UNSUPPORTED: d must be 32, 64, 96, 128 or 256 (64 or 128 for the fp32 and unfused paths), mask_kind 0 or 1, "
                    "scale finite and >= 0, Nk >= Nq with the causal mask";
         case FLAT_ERR_ALIGN: return "FLAT_ERR_ALIGN: pointers must be 16-byte aligned";
-        case FLAT_ERR_WORKSPACE: return "FLAT_ERR_WORKSPACE: workspace smaller than flat_attn_unfused_workspace_bytes()";
+        case FLAT_ERR_WORKSPACE:
+            return "FLAT_ERR_WORKSPACE: a workspace is smaller than the matching *_workspace_bytes() call says, or the request needs "
+                   "more than the built-in scratch buffer of flat_attn_fwd_splitkv_static holds";
         case FLAT_ERR_HIP: return "FLAT_ERR_HIP: the HIP runtime refused a launch";
-        case FLAT_ERR_ALIAS: return "FLAT_ERR_ALIAS: output or workspace overlaps another buffer";
+        case FLAT_ERR_ALIAS: return "FLAT_ERR_ALIAS: an output, workspace or sink overlaps another buffer";
         default: return "unknown flat_status";
     }
 }

@@ -56,3 +56,32 @@ def test_static_scratch_form_refuses_what_does_not_fit():
     fa.flat_attn_fwd_splitkv_static(q, k, k, o, 0.125, 1, None, 0)           # the library's choice is cut to what fits
     torch.cuda.synchronize()
     assert (o.float() == 0).all()
+
+
+def test_static_scratch_form_replays_from_a_hip_graph():
+    """What the entry point is for: captured into a HIP graph (nothing in it allocates or clears memory) and replayed,
+    with eager work between the replays; every replay equals the eager result bit for bit."""
+    import torch
+    B, H, Nq, Nk, d = 1, 8, 40, 6000, 64
+    q, k, v = rounded((B, H, Nq, d), 77, 0), rounded((B, H, Nk, d), 77, 1), rounded((B, H, Nk, d), 77, 2)
+    dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+    eager = torch.empty_like(dq)
+    fa.flat_attn_fwd_splitkv_static(dq, dk, dv, eager, 0.125, 1, None, 0)    # also resolves the buffer's address before the capture
+    torch.cuda.synchronize()
+    check_close(to_host_f64(eager), oracle.attention_cross(q, k, v, 0.125, 1), "bf16", "no-alloc eager")
+    out = torch.zeros_like(dq)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            fa.flat_attn_fwd_splitkv_static(dq, dk, dv, out, 0.125, 1, None, 0, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        other = torch.empty(B, H, 300, d, dtype=torch.bfloat16, device="cuda")
+        fa.flat_attn_fwd_splitkv_static(dk[:, :, :300].contiguous(), dk, dv, other, 0.125, 0, None, 3)   # eager use of the same buffer
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep}"

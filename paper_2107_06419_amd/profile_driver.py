@@ -18,6 +18,7 @@ def main() -> int:
     ap.add_argument("--cache", default="", help="H,Nq,Nk,d: instead of the above, a causal segment of Nq queries over Nk cached keys "
                                                 "through flat_attn_fwd_cross and flat_attn_fwd_splitkv")
     ap.add_argument("--mix", action="store_true", help="instead of the above, the four levels of the instruction-mix probe")
+    ap.add_argument("--mfma", default="", choices=["", "constant", "random"], help="instead of the above, the MFMA-only probe on these operands")
     args = ap.parse_args()
 
     import numpy as np
@@ -26,6 +27,13 @@ def main() -> int:
     import paper_2107_06419_amd as fa
     from paper_2107_06419_amd import synth
 
+    if args.mfma:
+        sink = torch.empty(fa.flat_attn_mfma_probe_sink_bytes() // 4, dtype=torch.float32, device="cuda")
+        for _ in range(args.reps):
+            fa.flat_attn_mfma_probe(sink, 16000, args.mfma == "random")
+        torch.cuda.synchronize()
+        print("profile_driver done mfma", args.mfma, flush=True)
+        return 0
     if args.mix:
         sink = torch.empty(fa.flat_attn_mix_probe_sink_bytes() // 4, dtype=torch.float32, device="cuda")
         src = torch.randn(fa.flat_attn_mix_probe_src_bytes() // 2, device="cuda").to(torch.bfloat16)

@@ -6,7 +6,7 @@ library is missing, every call raises.
 """
 from .binding import (FLAT_MASK_CAUSAL, FLAT_MASK_NONE, FlatAttnError, flat_attn_fwd, flat_attn_fwd_cross, flat_attn_fwd_blocksparse, flat_attn_fwd_f32,
                       flat_attn_status_string, flat_attn_unfused, flat_attn_unfused_workspace_bytes,
-                      flat_attn_version, library_path, load_library, flat_attn_mfma_probe, flat_attn_mfma_probe_flops,
+                      flat_attn_version, library_path, load_library, probe_library_path, load_probe_library, flat_attn_mfma_probe, flat_attn_mfma_probe_flops,
                       flat_attn_mfma_probe_sink_bytes, FlatTileShape, flat_attn_tile_shape_count,
                       flat_attn_tile_shape_get, flat_attn_tile_shape_occupancy, flat_attn_fwd_tile, flat_attn_mix_probe,
                       flat_attn_mix_probe_flops, flat_attn_mix_probe_sink_bytes, flat_attn_mix_probe_src_bytes,
@@ -15,7 +15,7 @@ from .binding import (FLAT_MASK_CAUSAL, FLAT_MASK_NONE, FlatAttnError, flat_attn
 
 __all__ = ["FLAT_MASK_NONE", "FLAT_MASK_CAUSAL", "FlatAttnError", "flat_attn_fwd", "flat_attn_fwd_cross", "flat_attn_fwd_blocksparse", "flat_attn_fwd_f32",
            "flat_attn_unfused", "flat_attn_unfused_workspace_bytes", "flat_attn_status_string", "flat_attn_version",
-           "library_path", "load_library", "flat_attn_mfma_probe", "flat_attn_mfma_probe_flops",
+           "library_path", "load_library", "probe_library_path", "load_probe_library", "flat_attn_mfma_probe", "flat_attn_mfma_probe_flops",
            "flat_attn_mfma_probe_sink_bytes", "FlatTileShape", "flat_attn_tile_shape_count", "flat_attn_tile_shape_get",
            "flat_attn_tile_shape_occupancy", "flat_attn_fwd_tile", "flat_attn_mix_probe", "flat_attn_mix_probe_flops",
            "flat_attn_mix_probe_sink_bytes", "flat_attn_mix_probe_src_bytes", "flat_attn_fwd_splitkv",

@@ -15,7 +15,9 @@ FLAT_DTYPE_BF16 = 0
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libflat_attn.so")
+_PROBE_LIB_PATH = os.path.join(_HERE, "libflat_attn_probe.so")
 _lib = None
+_probe_lib = None
 
 
 class FlatAttnError(RuntimeError):
@@ -35,6 +37,42 @@ class FlatTileShape(ctypes.Structure):
 
 def library_path() -> str:
     return _LIB_PATH
+
+
+def probe_library_path() -> str:
+    return _PROBE_LIB_PATH
+
+
+def load_probe_library():
+    """Load libflat_attn_probe.so (the measurement aids of include/flat_attn_probe.h); raises if it has not been built."""
+    global _probe_lib
+    if _probe_lib is not None:
+        return _probe_lib
+    if not os.path.exists(_PROBE_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_PROBE_LIB_PATH} is missing: build it with `python -m paper_2107_06419_amd.build` (needs hipcc)")
+    try:
+        import torch  # noqa: F401  (same HIP runtime as the tensors)
+    except ImportError:
+        pass
+    lib = ctypes.CDLL(_PROBE_LIB_PATH)
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.flat_attn_mfma_probe_sink_bytes.restype = sz
+    lib.flat_attn_mfma_probe_sink_bytes.argtypes = []
+    lib.flat_attn_mfma_probe_flops.restype = ctypes.c_double
+    lib.flat_attn_mfma_probe_flops.argtypes = [i]
+    lib.flat_attn_mfma_probe.restype = i
+    lib.flat_attn_mfma_probe.argtypes = [vp, sz, i, i, vp]
+    lib.flat_attn_mix_probe_sink_bytes.restype = sz
+    lib.flat_attn_mix_probe_sink_bytes.argtypes = []
+    lib.flat_attn_mix_probe_src_bytes.restype = sz
+    lib.flat_attn_mix_probe_src_bytes.argtypes = []
+    lib.flat_attn_mix_probe_flops.restype = ctypes.c_double
+    lib.flat_attn_mix_probe_flops.argtypes = [i]
+    lib.flat_attn_mix_probe.restype = i
+    lib.flat_attn_mix_probe.argtypes = [vp, sz, vp, sz, i, i, vp]
+    _probe_lib = lib
+    return lib
 
 
 def load_library():
@@ -81,20 +119,6 @@ def load_library():
     lib.flat_attn_tile_shape_occupancy.argtypes = [i, i]
     lib.flat_attn_fwd_tile.restype = i
     lib.flat_attn_fwd_tile.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, i, vp]
-    lib.flat_attn_mfma_probe_sink_bytes.restype = sz
-    lib.flat_attn_mfma_probe_sink_bytes.argtypes = []
-    lib.flat_attn_mfma_probe_flops.restype = ctypes.c_double
-    lib.flat_attn_mfma_probe_flops.argtypes = [i]
-    lib.flat_attn_mfma_probe.restype = i
-    lib.flat_attn_mfma_probe.argtypes = [vp, sz, i, i, vp]
-    lib.flat_attn_mix_probe_sink_bytes.restype = sz
-    lib.flat_attn_mix_probe_sink_bytes.argtypes = []
-    lib.flat_attn_mix_probe_src_bytes.restype = sz
-    lib.flat_attn_mix_probe_src_bytes.argtypes = []
-    lib.flat_attn_mix_probe_flops.restype = ctypes.c_double
-    lib.flat_attn_mix_probe_flops.argtypes = [i]
-    lib.flat_attn_mix_probe.restype = i
-    lib.flat_attn_mix_probe.argtypes = [vp, sz, vp, sz, i, i, vp]
     lib.flat_attn_status_string.restype = ctypes.c_char_p
     lib.flat_attn_status_string.argtypes = [i]
     lib.flat_attn_version.restype = i
@@ -280,31 +304,31 @@ def flat_attn_fwd_tile(Q, K, V, O, scale: float, mask_kind: int, tile_shape: int
 
 
 def flat_attn_mfma_probe_sink_bytes() -> int:
-    return int(load_library().flat_attn_mfma_probe_sink_bytes())
+    return int(load_probe_library().flat_attn_mfma_probe_sink_bytes())
 
 
 def flat_attn_mfma_probe_flops(iters: int) -> float:
-    return float(load_library().flat_attn_mfma_probe_flops(int(iters)))
+    return float(load_probe_library().flat_attn_mfma_probe_flops(int(iters)))
 
 
 def flat_attn_mfma_probe(sink, iters: int, random_operands: bool, stream=None) -> None:
     """MFMA-only throughput probe; `sink` is a device tensor of at least flat_attn_mfma_probe_sink_bytes() bytes."""
     if not sink.is_cuda or not sink.is_contiguous():
         raise ValueError("sink must be a contiguous GPU tensor")
-    _check(load_library().flat_attn_mfma_probe(sink.data_ptr(), sink.numel() * sink.element_size(), int(iters),
+    _check(load_probe_library().flat_attn_mfma_probe(sink.data_ptr(), sink.numel() * sink.element_size(), int(iters),
                                                1 if random_operands else 0, _stream_handle(stream)))
 
 
 def flat_attn_mix_probe_sink_bytes() -> int:
-    return int(load_library().flat_attn_mix_probe_sink_bytes())
+    return int(load_probe_library().flat_attn_mix_probe_sink_bytes())
 
 
 def flat_attn_mix_probe_src_bytes() -> int:
-    return int(load_library().flat_attn_mix_probe_src_bytes())
+    return int(load_probe_library().flat_attn_mix_probe_src_bytes())
 
 
 def flat_attn_mix_probe_flops(iters: int) -> float:
-    return float(load_library().flat_attn_mix_probe_flops(int(iters)))
+    return float(load_probe_library().flat_attn_mix_probe_flops(int(iters)))
 
 
 def flat_attn_mix_probe(sink, src, level: int, iters: int, stream=None) -> None:
@@ -312,5 +336,5 @@ def flat_attn_mix_probe(sink, src, level: int, iters: int, stream=None) -> None:
     flat_attn_mix_probe_sink_bytes() / flat_attn_mix_probe_src_bytes() bytes."""
     if not sink.is_cuda or not sink.is_contiguous() or not src.is_cuda or not src.is_contiguous():
         raise ValueError("sink and src must be contiguous GPU tensors")
-    _check(load_library().flat_attn_mix_probe(sink.data_ptr(), sink.numel() * sink.element_size(), src.data_ptr(),
+    _check(load_probe_library().flat_attn_mix_probe(sink.data_ptr(), sink.numel() * sink.element_size(), src.data_ptr(),
                                               src.numel() * src.element_size(), int(level), int(iters), _stream_handle(stream)))

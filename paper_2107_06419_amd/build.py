@@ -1,4 +1,5 @@
-"""Build the HIP library in-tree: paper_2107_06419_amd/libflat_attn.so (gfx950 only)."""
+"""Build the HIP libraries in-tree (gfx950 only): paper_2107_06419_amd/libflat_attn.so, its fully synchronised
+checking build libflat_attn_sync.so, and the measurement aids libflat_attn_probe.so."""
 from __future__ import annotations
 
 import os
@@ -11,7 +12,10 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflat_attn.so")
 SOURCES = ["flat_api.hip", "flat_fwd_bf16.hip", "flat_fwd_bf16_shapes_d64a.hip", "flat_fwd_bf16_shapes_d64b.hip",
-           "flat_fwd_bf16_shapes_d128.hip", "flat_fwd_bf16_shapes_dx.hip", "flat_splitkv.hip", "flat_plan.hip", "flat_tiles.hip", "flat_fwd_f32.hip", "flat_unfused.hip", "flat_probe.hip"]
+           "flat_fwd_bf16_shapes_d128.hip", "flat_fwd_bf16_shapes_dx.hip", "flat_splitkv.hip", "flat_plan.hip", "flat_tiles.hip", "flat_fwd_f32.hip", "flat_unfused.hip"]
+# the measurement aids live in a library of their own
+PROBE_LIB = os.path.join(HERE, "libflat_attn_probe.so")
+PROBE_SOURCES = ["flat_probe.hip", "flat_probe_api.hip"]
 # packed fp32 VALU instructions are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
@@ -46,11 +50,13 @@ def build_library(verbose: bool = True) -> str:
     """Compile every kernel source for gfx950 and link the shared library. Always recompiles."""
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=8) as pool:
-        jobs = [pool.submit(_compile, s) for s in SOURCES] + [pool.submit(_compile, s, True) for s in SYNC_SOURCES]
+        jobs = ([pool.submit(_compile, s) for s in SOURCES] + [pool.submit(_compile, s, True) for s in SYNC_SOURCES] +
+                [pool.submit(_compile, s) for s in PROBE_SOURCES])
         objs = [j.result() for j in jobs]
-    plain, sync = objs[:len(SOURCES)], objs[len(SOURCES):]
+    plain, sync = objs[:len(SOURCES)], objs[len(SOURCES):len(SOURCES) + len(SYNC_SOURCES)]
+    probe = objs[len(SOURCES) + len(SYNC_SOURCES):]
     sync_objs = [o for s, o in zip(SOURCES, plain) if s not in SYNC_SOURCES] + sync
-    for lib, parts in ((LIB, plain), (SYNC_LIB, sync_objs)):
+    for lib, parts in ((LIB, plain), (SYNC_LIB, sync_objs), (PROBE_LIB, probe)):
         tmp = lib + f".tmp{os.getpid()}"
         subprocess.check_call([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *parts])
         os.replace(tmp, lib)

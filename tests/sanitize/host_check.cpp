@@ -1,6 +1,6 @@
 // Host-only check run under AddressSanitizer and UndefinedBehaviorSanitizer (tests/test_sanitizers_host.py
 // builds and runs it; no GPU, no HIP runtime).  It links
-//   * the argument-validation half of the C ABI (csrc/flat_api.hip and csrc/flat_plan.hip compiled as plain C++) against stub
+//   * the argument-validation half of the C ABI (csrc/flat_api.hip, csrc/flat_plan.hip and csrc/flat_probe_api.hip compiled as plain C++) against stub
 //     launchers that only count calls, and walks its error paths with pointers that are never dereferenced;
 //   * the CPU oracle, and runs every entry point of it on small problems with row subsets, key counts, block
 //     patterns and several threads, comparing with a direct long-double evaluation.
@@ -14,6 +14,7 @@
 #include <vector>
 
 #include "../../include/flat_attn.h"
+#include "../../include/flat_attn_probe.h"
 #include "../../paper_2107_06419_amd/csrc/flat_launch.hpp"
 
 // ---- stub launchers: the validation code must never get here with bad arguments --------------------------------------

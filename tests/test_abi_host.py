@@ -11,30 +11,39 @@ import paper_2107_06419_amd as fa
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "flat_attn.h")).read()
+def declared_functions(header="flat_attn.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(flat_attn_\w+)\s*\(", text)))
 
 
+# every header under include/ and the library that implements it
+HEADERS = {"flat_attn.h": fa.library_path, "flat_attn_probe.h": fa.probe_library_path}
+
+
 def test_header_declares_the_expected_entry_points():
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == sorted(HEADERS)
     names = declared_functions()
     for must in ("flat_attn_fwd", "flat_attn_fwd_f32", "flat_attn_unfused", "flat_attn_unfused_workspace_bytes",
                  "flat_attn_status_string", "flat_attn_version"):
         assert must in names
+    assert not [n for n in names if "probe" in n], "the attention library carries no measurement aids"
+    assert all("probe" in n for n in declared_functions("flat_attn_probe.h"))
 
 
 def test_library_exports_every_declared_symbol():
-    if not os.path.exists(fa.library_path()):
-        pytest.fail(f"{fa.library_path()} not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
-    lib = ctypes.CDLL(fa.library_path())
-    for name in declared_functions():
-        assert hasattr(lib, name), f"libflat_attn.so does not export {name}"
+    for header, path in HEADERS.items():
+        if not os.path.exists(path()):
+            pytest.fail(f"{path()} not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        lib = ctypes.CDLL(path())
+        for name in declared_functions(header):
+            assert hasattr(lib, name), f"{os.path.basename(path())} does not export {name}"
 
 
 def test_binding_has_the_same_names():
-    for name in declared_functions():
-        assert hasattr(fa, name), f"python binding lacks {name}"
+    for header in HEADERS:
+        for name in declared_functions(header):
+            assert hasattr(fa, name), f"python binding lacks {name}"
 
 
 def test_version_and_status_strings():
@@ -151,7 +160,7 @@ def test_blocksparse_entry_point_validation():
 
 
 def test_mix_probe_validation():
-    lib = fa.load_library()
+    lib = fa.load_probe_library()
     need_sink, need_src = fa.flat_attn_mix_probe_sink_bytes(), fa.flat_attn_mix_probe_src_bytes()
     assert need_sink == 512 * 256 * 4 and need_src == 2 * 64 * 8192
     assert fa.flat_attn_mix_probe_flops(1) == 512 * 4 * 8 * 16 * 32768.0 and fa.flat_attn_mix_probe_flops(0) == 0.0

@@ -1,5 +1,5 @@
 """AddressSanitizer + UndefinedBehaviorSanitizer over the host-side code: the C ABI's argument validation
-(csrc/flat_api.hip and csrc/flat_plan.hip compiled as plain C++ against stub launchers) and the CPU oracle, driven by
+(csrc/flat_api.hip, flat_plan.hip and flat_probe_api.hip compiled as plain C++ against stub launchers) and the CPU oracle, driven by
 tests/sanitize/host_check.cpp.  No GPU and no HIP runtime are involved."""
 import os
 import shutil
@@ -22,6 +22,7 @@ def test_validation_code_and_oracle_are_clean_under_asan_and_ubsan():
                "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-pthread", "-o", exe,
                "-x", "c++", os.path.join(ROOT, "paper_2107_06419_amd", "csrc", "flat_api.hip"),
                os.path.join(ROOT, "paper_2107_06419_amd", "csrc", "flat_plan.hip"),
+               os.path.join(ROOT, "paper_2107_06419_amd", "csrc", "flat_probe_api.hip"),
                os.path.join(ROOT, "oracle", "flat_oracle.cpp"), os.path.join(ROOT, "tests", "sanitize", "host_check.cpp")]
         built = subprocess.run(cmd, capture_output=True, text=True)
         assert built.returncode == 0, built.stderr[-4000:]

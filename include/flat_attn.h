@@ -94,7 +94,7 @@ int flat_attn_fwd_cross(const void* Q, const void* K, const void* V, void* O,
  * (reference maximum, row sum, unnormalised output, all fp32) in `workspace`, and a second kernel merges them.
  * Same arguments, masks, key counts and tolerance as flat_attn_fwd_cross, plus
  *   n_splits: parts the key sequence is divided into, clamped to [1, number of key tiles]; <= 0 lets the library
- *     choose (about two workgroups per compute-unit slot, at least 8 key tiles per split).
+ *     choose (one workgroup per compute-unit slot, at least 8 key tiles per split).
  *     flat_attn_fwd_splitkv_splits returns the number actually used (or a negative flat_status).
  *   workspace: device, 16-byte aligned, at least flat_attn_fwd_splitkv_workspace_bytes() bytes (same B, H, Nq,
  *     Nk, d, n_splits; 0 means the arguments are invalid), overwritten; it must not overlap any other buffer

@@ -6,19 +6,27 @@ namespace flat {
 
 namespace {
 // The tile shape a split-keys launch uses: rows per workgroup, keys per tile, padded head dimension, workgroups that
-// fit a compute unit.  Every workgroup multiplies a full tile of `rows` rows whatever Nq is, so at d = 64 (where the
-// template has them: flat_splitkv.hip) few query rows take a shape with fewer rows.
+// fit a compute unit.  Every workgroup multiplies a full tile of `rows` rows whatever Nq is, so few query rows take a shape
+// with fewer rows where flat_splitkv.hip builds one.
 struct Geometry { int rows, keys, dp, per_cu; };
 bool geometry(int d, int Nq, Geometry* g) {
     switch (d) {
-        case 32: *g = {256, 64, 32, 2}; return true;
+        case 32:
+            if (Nq <= 32) *g = {32, 64, 32, 6};
+            else if (Nq <= 64) *g = {64, 64, 32, 4};
+            else if (Nq <= 128) *g = {128, 64, 32, 2};
+            else *g = {256, 64, 32, 2};
+            return true;
         case 64:
             if (Nq <= 32) *g = {32, 64, 64, 3};
             else if (Nq <= 64) *g = {64, 64, 64, 2};
             else if (Nq <= 128) *g = {128, 64, 64, 2};
             else *g = {256, 64, 64, 2};
             return true;
-        case 96: *g = {256, 64, 128, 1}; return true;
+        case 96:
+            if (Nq <= 128) *g = {128, 64, 128, 1};
+            else *g = {256, 64, 128, 1};
+            return true;
         case 128:
             if (Nq <= 128) *g = {128, 64, 128, 1};
             else *g = {256, 64, 128, 1};
@@ -41,9 +49,10 @@ bool split_plan(int BH, int Nq, int Nk, int d, int n_splits_wanted, SplitPlan* o
     p.n_row_blocks = (int)(((long long)Nq + g.rows - 1) / g.rows);
     p.n_tiles = (int)(((long long)Nk + g.keys - 1) / g.keys);
     long long s = n_splits_wanted;
-    if (s <= 0) {  // fill the chip about twice over, but keep every split long enough to pay for itself
+    if (s <= 0) {  // one workgroup per slot of the chip (measured: more only adds partial results to write and merge), but
+                   // keep every split long enough to pay for itself
         const long long blocks = (long long)BH * p.n_row_blocks;
-        s = (2 * kComputeUnits * g.per_cu + blocks - 1) / blocks;
+        s = (kComputeUnits * g.per_cu + blocks - 1) / blocks;
         const long long longest = (p.n_tiles + kMinTilesPerSplit - 1) / kMinTilesPerSplit;
         if (s > longest) s = longest;
     }

@@ -98,10 +98,11 @@ static void check_validation() {
     EXPECT(flat_attn_fwd_cross(Q, K, V, O, 1, 1, 2147483647, 2147483647, 256, 1.f, 0, nullptr, nullptr) == FLAT_ERR_SHAPE);
 
     // split keys: the plan is real host code (csrc/flat_plan.hip), the launch is a stub
-    EXPECT(flat_attn_fwd_splitkv_splits(1, 16, 256, 65536, 64, 0) == 64);
+    EXPECT(flat_attn_fwd_splitkv_splits(1, 16, 256, 65536, 64, 0) == 32);      // 512 slots for 16 row blocks
     EXPECT(flat_attn_fwd_splitkv_splits(1, 16, 256, 65536, 64, 7) == 7);
     EXPECT(flat_attn_fwd_splitkv_splits(1, 1, 1, 100, 64, 9) == 2);          // two tiles: at most two splits
-    EXPECT(flat_attn_fwd_splitkv_splits(1, 16, 1, 65536, 64, 0) == 94);      // 32-row shape, 3 workgroups per compute unit: 96 wanted,
+    EXPECT(flat_attn_fwd_splitkv_splits(1, 16, 1, 65536, 64, 0) == 47);      // 32-row shape, 3 workgroups per compute unit: 48 wanted, 22 tiles each
+    EXPECT(flat_attn_fwd_splitkv_splits(1, 16, 1, 65536, 32, 0) == 94);      // d = 32: 6 per compute unit, 96 wanted,
     EXPECT(flat_attn_fwd_splitkv_splits(1, 16, 1, 65536, 64, 96) == 94);     // 11 tiles each, and 94 such splits cover the 1024 tiles
     EXPECT(flat_attn_fwd_splitkv_workspace_bytes(1, 16, 1, 65536, 64, 96) == (size_t)16 * 94 * 32 * 66 * 4);
     EXPECT(flat_attn_fwd_splitkv_splits(1, 1, 1, 100, 80, 0) == FLAT_ERR_UNSUPPORTED);

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflat_attn.so")
 SOURCES = ["flat_api.hip", "flat_fwd_bf16.hip", "flat_fwd_bf16_shapes_d64a.hip", "flat_fwd_bf16_shapes_d64b.hip",
-           "flat_fwd_bf16_shapes_d128.hip", "flat_fwd_bf16_shapes_dx.hip", "flat_splitkv.hip", "flat_plan.hip", "flat_tiles.hip", "flat_fwd_f32.hip", "flat_unfused.hip"]
+           "flat_fwd_bf16_shapes_d64c.hip", "flat_fwd_bf16_shapes_d128.hip", "flat_fwd_bf16_shapes_dx.hip", "flat_splitkv.hip", "flat_plan.hip", "flat_tiles.hip", "flat_fwd_f32.hip", "flat_unfused.hip"]
 # the measurement aids live in a library of their own
 PROBE_LIB = os.path.join(HERE, "libflat_attn_probe.so")
 PROBE_SOURCES = ["flat_probe.hip", "flat_probe_api.hip"]

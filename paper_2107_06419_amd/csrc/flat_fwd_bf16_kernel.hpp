@@ -47,7 +47,8 @@ constexpr bool kSyncEveryPhase = false;
 // Head dimensions.  D is the head dimension of the tensors in memory (32, 64, 96, 128 or 256); the tiles in LDS
 // and the matrix products use DP = D rounded up to a power of two (96 -> 128: the missing columns of Q are zero,
 // so whatever the padded K columns hold drops out of the logits, and the padded output columns are not stored).
-// A tile holds BC keys: 64 (two 32-key blocks), or 32 at d = 256, where 64 keys of K and V would take 64 KiB.
+// A tile holds BC keys: 64 (two 32-key blocks), or 32 at d = 256, where 64 keys of K and V would take 64 KiB; a tile
+// shape may ask for another multiple of 32 (BCX: 32, 64 or 128) so that this axis of the map space can be measured too.
 //
 // LDS tile layout.  Rows are stored unpadded (ROWB = 2 DP bytes) because tiles arrive by
 // global_load_lds_dwordx4, which writes the 64 lanes of a wavefront to 1024 contiguous LDS bytes
@@ -55,11 +56,11 @@ constexpr bool kSyncEveryPhase = false;
 // chunk index within a row: chunk c of row r lives in slot c ^ swz(r).  The LDS serves 256 bytes
 // per clock: a ds_read_b128 touches 16 rows at one chunk index per clock, a ds_read_b64_tr_b16
 // touches 4 rows x 64 bytes; swz() is chosen so that both patterns hit every bank once.
-template <int D, int STAGES, int NW>
+template <int D, int STAGES, int NW, int BCX = 0>
 struct Bf16Cfg {
     static_assert(D == 32 || D == 64 || D == 96 || D == 128 || D == 256, "head dimension not built");
     static constexpr int DP = D == 96 ? 128 : D;      // head dimension of the tiles and products
-    static constexpr int BC = D == 256 ? 32 : 64;     // keys per tile
+    static constexpr int BC = BCX ? BCX : (D == 256 ? 32 : 64);  // keys per tile
     static constexpr int ROWB = DP * 2;               // bytes per row in LDS
     static constexpr int GROWB = D * 2;               // bytes per row in global memory
     static constexpr int CHUNKS = ROWB / 16;          // 16-byte chunks per LDS row
@@ -108,17 +109,19 @@ constexpr int kMaxSparseTiles = 2048;  // block-sparse: listed tiles per row blo
 // unnormalised result (reference maximum, row sum, accumulators) in a workspace for split_merge_kernel.
 constexpr int kDense = 0, kSparse = 1, kSplit = 2;
 
-template <int D, int QB, int NW, int STAGES, bool CAUSAL, int MODE = kDense>
+template <int D, int QB, int NW, int STAGES, bool CAUSAL, int MODE = kDense, int BCX = 0>
 __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 2) void fwd_bf16_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K,
                                                           const bf16* __restrict__ V, bf16* __restrict__ O,
                                                           const Bf16Problem prob, int n_qtiles, int n_blocks,
                                                           int blocks_per_xcd, float c) {
-    using C = Bf16Cfg<D, STAGES, NW>;
+    using C = Bf16Cfg<D, STAGES, NW, BCX>;
     constexpr bool SPARSE = MODE == kSparse, SPLIT = MODE == kSplit;
     constexpr int DP = C::DP, QW = 32 * QB, BR = NW * QW, BC = C::BC, DS = DP / 16, DB = DP / 32;
     constexpr int KB = BC / 32;    // 32-key blocks per tile
     constexpr int KB64 = 64 / BC;  // tiles per 64 keys (the unit of a block-sparse list)
-    static_assert(KB == 2 || STAGES % 2 == 0, "with one block per tile the unrolled loop needs an even ring");
+    static_assert(KB == 1 || KB == 2 || KB == 4, "a tile is one, two or four 32-key blocks");
+    static_assert(KB != 1 || STAGES % 2 == 0, "with one block per tile the unrolled loop needs an even ring");
+    static_assert(!SPARSE || KB64 >= 1, "block-sparse lists name 64-key tiles");
     constexpr int LOADS_PER_TILE = 2 * C::LOADS;  // DMA instructions per wavefront per tile (K and V)
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -609,23 +612,27 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
             __syncthreads();
         }
     };
-    // Two blocks per tile: the second step already reads K of the next tile, so the synchronisation sits between
-    // the two steps.  One block per tile: it sits before the tile's only step, and consecutive tiles alternate the
+    // Two or four blocks per tile: the last step already reads K of the next tile, so the synchronisation sits
+    // before it.  One block per tile: it sits before the tile's only step, and consecutive tiles alternate the
     // roles of the two logit / probability register sets (`odd`).
     auto tile_steps = [&](int j, int sj, bool masked, bool odd) __attribute__((always_inline)) {  // sj = j % STAGES
         const int sn = sj + 1 == STAGES ? 0 : sj + 1;       // stage of tile j+1
         // first 32-key block of the tile, as a key position / 32 (only the masked form of a step looks at it)
         const int kb0 = KB * (((SPARSE && masked) || SPLIT) ? tile_of(j) : j);
-        if (KB == 2) {
-            if (kTwoVSets)
-                step(kb0, sj, sj, masked, xA, xB, pB, vfB, pA, vfA);
-            else
-                step(kb0, sj, sj, masked, xA, xB, pB, vfA, pA, vfA);
-            sync_and_stream(j, sj);
-            if (kTwoVSets)
-                step(kb0 + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfB);
-            else
-                step(kb0 + 1, sj, sn, masked, xB, xA, pA, vfA, pB, vfA);
+        if (KB >= 2) {
+#pragma unroll
+            for (int i = 0; i < KB; i += 2) {
+                if (kTwoVSets)
+                    step(kb0 + i, sj, sj, masked, xA, xB, pB, vfB, pA, vfA);
+                else
+                    step(kb0 + i, sj, sj, masked, xA, xB, pB, vfA, pA, vfA);
+                const bool last = i + 2 == KB;
+                if (last) sync_and_stream(j, sj);
+                if (kTwoVSets)
+                    step(kb0 + i + 1, sj, last ? sn : sj, masked, xB, xA, pA, vfA, pB, vfB);
+                else
+                    step(kb0 + i + 1, sj, last ? sn : sj, masked, xB, xA, pA, vfA, pB, vfA);
+            }
         } else {
             sync_and_stream(j, sj);
             if (!odd) {
@@ -662,7 +669,7 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
     // remaining visible tiles and the partly masked ones (masking a fully visible tile changes nothing)
     int sj = 0;  // j is a multiple of STAGES here (even, where that matters)
     bool owed_in_a = false;  // one block per tile only: the last step left its probabilities in pA, not pB
-    if (KB == 2) {
+    if (KB >= 2) {
 #pragma unroll 1
         for (; j < n_act_tiles; ++j) {
             tile_steps(j, sj, true, false);
@@ -742,7 +749,7 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
     }
 }
 
-template <int D, int QB, int NW, int STAGES, bool CAUSAL, int MODE = kDense>
+template <int D, int QB, int NW, int STAGES, bool CAUSAL, int MODE = kDense, int BCX = 0>
 inline hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, float scale,
                              hipStream_t stream) {
     constexpr int BR = 32 * QB * NW;
@@ -750,8 +757,8 @@ inline hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* 
     const int n_qtiles = (prob.Nq + BR - 1) / BR * (MODE == kSplit ? prob.n_splits : 1);
     const int n_blocks = BH * n_qtiles;
     const int blocks_per_xcd = (n_blocks + 7) / 8;
-    auto kern = fwd_bf16_kernel<D, QB, NW, STAGES, CAUSAL, MODE>;
-    constexpr int lds = Bf16Cfg<D, STAGES, NW>::LDS_BYTES + (MODE == kSparse ? kMaxSparseTiles * (int)sizeof(int) : 0);
+    auto kern = fwd_bf16_kernel<D, QB, NW, STAGES, CAUSAL, MODE, BCX>;
+    constexpr int lds = Bf16Cfg<D, STAGES, NW, BCX>::LDS_BYTES + (MODE == kSparse ? kMaxSparseTiles * (int)sizeof(int) : 0);
     static std::atomic<uint64_t> attr_done{0};  // one flag per kernel instantiation
     hipError_t e = allow_dynamic_lds((const void*)kern, lds, &attr_done);
     if (e != hipSuccess) return e;
@@ -762,18 +769,18 @@ inline hipError_t launch_cfg(const void* Q, const void* K, const void* V, void* 
 
 // The two mask variants of one tile shape behind one call; defined here, instantiated explicitly by the
 // translation units that own the shapes (declared in flat_launch.hpp).
-template <int D, int QB, int NW, int STAGES>
+template <int D, int QB, int NW, int STAGES, int BCX>
 hipError_t launch_fwd_bf16_shape(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, float scale,
                                  int causal, hipStream_t stream) {
-    return causal ? launch_cfg<D, QB, NW, STAGES, true>(Q, K, V, O, BH, prob, scale, stream)
-                  : launch_cfg<D, QB, NW, STAGES, false>(Q, K, V, O, BH, prob, scale, stream);
+    return causal ? launch_cfg<D, QB, NW, STAGES, true, kDense, BCX>(Q, K, V, O, BH, prob, scale, stream)
+                  : launch_cfg<D, QB, NW, STAGES, false, kDense, BCX>(Q, K, V, O, BH, prob, scale, stream);
 }
 
 // Workgroups of this shape that fit one compute unit at a time (registers and LDS), as the runtime reports it.
-template <int D, int QB, int NW, int STAGES>
+template <int D, int QB, int NW, int STAGES, int BCX>
 hipError_t fwd_bf16_shape_occupancy(int* workgroups_per_cu) {
-    auto kern = fwd_bf16_kernel<D, QB, NW, STAGES, false>;
-    constexpr int lds = Bf16Cfg<D, STAGES, NW>::LDS_BYTES;
+    auto kern = fwd_bf16_kernel<D, QB, NW, STAGES, false, kDense, BCX>;
+    constexpr int lds = Bf16Cfg<D, STAGES, NW, BCX>::LDS_BYTES;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(workgroups_per_cu, kern, 64 * NW, lds);
@@ -786,9 +793,10 @@ hipError_t launch_fwd_bf16_sparse_shape(const void* Q, const void* K, const void
     return launch_cfg<D, QB, NW, STAGES, false, kSparse>(Q, K, V, O, BH, prob, scale, stream);
 }
 
-#define FLAT_INSTANTIATE_BF16_SHAPE(D, QB, NW, STAGES)                                                                      \
-    template hipError_t launch_fwd_bf16_shape<D, QB, NW, STAGES>(const void*, const void*, const void*, void*, int,         \
-                                                                 const Bf16Problem&, float, int, hipStream_t);             \
-    template hipError_t fwd_bf16_shape_occupancy<D, QB, NW, STAGES>(int*);
+#define FLAT_INSTANTIATE_BF16_SHAPE_BC(D, QB, NW, STAGES, BCX)                                                               \
+    template hipError_t launch_fwd_bf16_shape<D, QB, NW, STAGES, BCX>(const void*, const void*, const void*, void*, int,    \
+                                                                      const Bf16Problem&, float, int, hipStream_t);        \
+    template hipError_t fwd_bf16_shape_occupancy<D, QB, NW, STAGES, BCX>(int*);
+#define FLAT_INSTANTIATE_BF16_SHAPE(D, QB, NW, STAGES) FLAT_INSTANTIATE_BF16_SHAPE_BC(D, QB, NW, STAGES, 0)
 
 }  // namespace flat

@@ -85,10 +85,10 @@ hipError_t launch_fwd_bf16_tile(const void* Q, const void* K, const void* V, voi
                                 float scale, int causal, int index, hipStream_t stream);
 // One tile shape (D head dim, QB 32-row blocks per wavefront, NW wavefronts, STAGES ring depth): defined in
 // flat_fwd_bf16_kernel.hpp, instantiated by the flat_fwd_bf16*.hip translation units.
-template <int D, int QB, int NW, int STAGES>
+template <int D, int QB, int NW, int STAGES, int BCX = 0>  // BCX: keys per tile, 0 = the head dimension's usual tile
 hipError_t launch_fwd_bf16_shape(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, float scale,
                                  int causal, hipStream_t stream);
-template <int D, int QB, int NW, int STAGES>
+template <int D, int QB, int NW, int STAGES, int BCX = 0>
 hipError_t fwd_bf16_shape_occupancy(int* workgroups_per_cu);
 
 hipError_t launch_fwd_f32(const float* Q, const float* K, const float* V, float* O, int BH, int N, int d, float scale,

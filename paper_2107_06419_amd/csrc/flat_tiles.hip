@@ -18,15 +18,17 @@ struct Entry {
     OccupancyFn occupancy;
 };
 
-template <int D, int QB, int NW, int STAGES>
+template <int D, int QB, int NW, int STAGES, int BCX = 0>
 constexpr Entry entry() {
-    constexpr int DP = D == 96 ? 128 : D, BC = D == 256 ? 32 : 64;  // as in Bf16Cfg: padded row length, keys per tile
+    constexpr int DP = D == 96 ? 128 : D, BC = BCX ? BCX : (D == 256 ? 32 : 64);  // as in Bf16Cfg: padded row length, keys per tile
     return Entry{TileShape{D, 32 * QB * NW, BC, NW, 32 * QB, STAGES, STAGES * 2 * BC * DP * 2},
-                 &launch_fwd_bf16_shape<D, QB, NW, STAGES>, &fwd_bf16_shape_occupancy<D, QB, NW, STAGES>};
+                 &launch_fwd_bf16_shape<D, QB, NW, STAGES, BCX>, &fwd_bf16_shape_occupancy<D, QB, NW, STAGES, BCX>};
 }
 
 const Entry kD64[] = {entry<64, 2, 4, 4>(), entry<64, 2, 4, 3>(), entry<64, 2, 4, 6>(), entry<64, 2, 8, 4>(),
-                      entry<64, 1, 8, 4>(), entry<64, 1, 4, 4>(), entry<64, 2, 2, 4>(), entry<64, 1, 4, 3>()};
+                      entry<64, 1, 8, 4>(), entry<64, 1, 4, 4>(), entry<64, 2, 2, 4>(), entry<64, 1, 4, 3>(),
+                      // the key-tile axis: 128 keys per tile (512-row and 256-row workgroups), 32 keys per tile
+                      entry<64, 2, 8, 3, 128>(), entry<64, 2, 8, 4, 128>(), entry<64, 2, 4, 3, 128>(), entry<64, 2, 4, 6, 32>()};
 const Entry kD128[] = {entry<128, 1, 8, 3>(), entry<128, 1, 8, 4>(), entry<128, 1, 4, 3>(), entry<128, 2, 4, 3>()};
 const Entry kD32[] = {entry<32, 2, 4, 4>()};
 const Entry kD96[] = {entry<96, 1, 8, 3>()};

@@ -86,3 +86,28 @@ def test_release_and_fully_synchronised_builds_agree_on_cached_keys():
         assert rc == 0
         torch.cuda.synchronize()
         assert torch.equal(rel.view(torch.int16), chk.view(torch.int16))
+
+
+@pytest.mark.parametrize("d", [32, 64, 96, 128, 256])
+def test_release_and_fully_synchronised_builds_agree_for_every_tile_shape(d):
+    """Every shape of the tile table (other ring depths, wavefront counts and keys per tile than the default) keeps its
+    own wait counts and barrier placement, so each is compared with its fully synchronised build."""
+    import torch
+    lib = _sync_lib()
+    vp, i, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    lib.flat_attn_fwd_tile.restype = i
+    lib.flat_attn_fwd_tile.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, i, vp]
+    for index in range(fa.flat_attn_tile_shape_count(d)):
+        for N, mask in ((1777, 0), (2100, 1)):
+            w = synth.custom(f"sync_tile_{d}_{index}_{N}", 1, 3, N, d, "bf16", mask, seed=977 + d + index + N)
+            q, k, v = synth.make_qkv(w)
+            dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+            rel, chk = torch.full_like(dq, float("nan")), torch.full_like(dq, float("nan"))
+            print(f"case sync build tile shape {index} {w}", flush=True)
+            fa.flat_attn_fwd_tile(dq, dk, dv, rel, w.scale, w.mask, index)
+            rc = lib.flat_attn_fwd_tile(dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), chk.data_ptr(), w.B, w.H, w.N, w.d, w.scale,
+                                        w.mask, index, torch.cuda.current_stream().cuda_stream)
+            assert rc == 0
+            torch.cuda.synchronize()
+            assert torch.isfinite(rel.float()).all()
+            assert torch.equal(rel.view(torch.int16), chk.view(torch.int16))

@@ -553,3 +553,52 @@ def test_reference_max_is_raised_when_logits_grow_along_the_sequence(d, mask):
     k[:, :, 900, :] *= 8.0             # exactly representable; a jump of hundreds of log2 units at key 900
     got = to_host_f64(run_entry("fused", w, q, k, v))
     check_close(got, oracle_rows(w, q, k, v), "bf16", w.name)
+
+
+def test_host_threads_launching_on_their_own_streams_get_the_single_threaded_results():
+    """The library keeps no state between calls apart from once-per-kernel launch attributes, so host threads may
+    call it at the same time on different streams.  Each thread runs problems of its own head size (so their first
+    launches of a kernel coincide) several times; every result must equal, bit for bit, the one computed alone."""
+    import threading
+    import torch
+    import paper_2107_06419_amd as fa
+    jobs = []
+    for t, (d, N, mask) in enumerate([(64, 1333, 0), (128, 900, 1), (32, 2050, 1), (96, 777, 0), (256, 640, 1), (64, 4100, 1)]):
+        w = synth.custom(f"thread_{t}", 1, 3, N, d, "bf16", mask, seed=8800 + t)
+        q, k, v = synth.make_qkv(w)
+        jobs.append((w, [to_device(x, "bf16") for x in (q, k, v)]))
+    alone = []
+    for w, (dq, dk, dv) in jobs:
+        out = torch.empty_like(dq)
+        fa.flat_attn_fwd(dq, dk, dv, out, w.scale, w.mask)
+        alone.append(out)
+    torch.cuda.synchronize()
+    results = [[] for _ in jobs]
+    errors = []
+
+    def worker(i):
+        try:
+            w, (dq, dk, dv) = jobs[i]
+            stream = torch.cuda.Stream()
+            stream.wait_stream(torch.cuda.default_stream())
+            with torch.cuda.stream(stream):  # the poison fill and the call share the stream
+                for _ in range(8):
+                    out = torch.full_like(dq, float("nan"))
+                    fa.flat_attn_fwd(dq, dk, dv, out, w.scale, w.mask, stream=stream)
+                    results[i].append(out)
+            stream.synchronize()
+        except Exception as e:  # noqa: BLE001  (reported by the main thread)
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(len(jobs))]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=100)
+        assert not th.is_alive(), "a launching thread did not finish"
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for i, outs in enumerate(results):
+        assert len(outs) == 8
+        for out in outs:
+            assert torch.equal(out.view(torch.int16), alone[i].view(torch.int16)), f"thread {i}"

@@ -174,8 +174,8 @@ int flat_attn_unfused(const void* Q, const void* K, const void* V, void* O,
  * cost model (section 6.1) and discusses what the row granularity trades (section 5.3: fewer query rows per
  * tile re-fetch the keys more often and fill the compute array less; more rows need more on-chip memory).
  * Here the exploration is done by measurement: the library is built with several shapes per head dimension,
- * flat_attn_fwd uses index 0 (index 3 for d = 64 with the causal mask once B*H*ceil(N/512) >= 512, where the
- * measured sweep puts it ahead), and flat_attn_fwd_tile runs any of them so that the choice can be re-timed.
+ * flat_attn_fwd uses index 0 (no other shape is ahead of it by more than the run-to-run spread over the measured
+ * problems), and flat_attn_fwd_tile runs any of them so that the choice can be re-timed.
  *   flat_attn_tile_shape_count(d): number of shapes for head dimension d (0 if d is not one of 32, 64, 96, 128, 256).
  *   flat_attn_tile_shape_get: fills *out (HOST pointer) for 0 <= index < count; FLAT_ERR_SHAPE otherwise.
  *   flat_attn_tile_shape_occupancy: workgroups of that shape resident per compute unit on the current

@@ -212,30 +212,7 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
         return KB64 == 1 ? sp_ids[j] : sp_ids[j / KB64] * KB64 + j % KB64;
     };
 
-    // reference max of each row = c * (q . k_first), k_first = the first key the row block sees (key 0 unless
-    // block-sparse), from the fragments already in registers
-    float m[QB];
-    {
-        float k0[DS][8];
-        const int first_key = SPLIT ? min(t0 * BC, N - 1) : (SPARSE && sp_count > 0) ? sp_ids[0] * 64 : 0;
-#pragma unroll
-        for (int ds = 0; ds < DS; ++ds) {
-            uint4v kv = {0, 0, 0, 0};
-            if (ds * 16 + half * 8 < D) kv = *(const uint4v*)(Kh + (size_t)first_key * C::GROWB + ds * 32 + half * 16);
-            const bf16x8 kb8 = __builtin_bit_cast(bf16x8, kv);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) k0[ds][e] = (float)kb8[e];
-        }
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            float dot = 0.f;
-#pragma unroll
-            for (int ds = 0; ds < DS; ++ds)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) dot = __builtin_fmaf((float)qf[qb][ds][e], k0[ds][e], dot);
-            m[qb] = halves_sum(dot) * c;
-        }
-    }
+    float m[QB];  // reference max of each row, set in the prologue below
 
     floatx16 oacc[QB][DB];
     float lsum[QB];
@@ -410,11 +387,36 @@ __global__ __launch_bounds__(64 * NW, ((D == 128 && QB == 2) || D == 256) ? 1 : 
                 for (int r = 0; r < 16; ++r) oacc[qb][db][r] *= alpha;
         }
     };
-    // ---- prologue: fill STAGES-1 stages.  The full wait also retires the Q loads above, so that no
-    // wait on them is left inside the loops (it would drain the prefetch ring every iteration).
+    // ---- prologue: fill STAGES-1 stages.  The full wait at its end also retires the Q loads above, so that no
+    // wait on them is left inside the loops (it would drain the prefetch ring every iteration).  The streaming
+    // loads go out before the first-key loads below are waited for, so that a workgroup's start is one memory round
+    // trip, not two in a row (short sequences consist of little else).
 #pragma unroll
     for (int t = 0; t < STAGES - 1; ++t)
         if (t < n_tiles) issue_tile_loads(t, t);
+    // reference max of each row = c * (q . k_first), k_first = the first key the row block sees (key 0 unless
+    // block-sparse or split), from the Q fragments already in registers
+    {
+        float k0[DS][8];
+        const int first_key = SPLIT ? min(t0 * BC, N - 1) : (SPARSE && sp_count > 0) ? sp_ids[0] * 64 : 0;
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) {
+            uint4v kv = {0, 0, 0, 0};
+            if (ds * 16 + half * 8 < D) kv = *(const uint4v*)(Kh + (size_t)first_key * C::GROWB + ds * 32 + half * 16);
+            const bf16x8 kb8 = __builtin_bit_cast(bf16x8, kv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) k0[ds][e] = (float)kb8[e];
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            float dot = 0.f;
+#pragma unroll
+            for (int ds = 0; ds < DS; ++ds)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot = __builtin_fmaf((float)qf[qb][ds][e], k0[ds][e], dot);
+            m[qb] = halves_sum(dot) * c;
+        }
+    }
     wait_vm<0>();
     __syncthreads();
 

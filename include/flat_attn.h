@@ -174,8 +174,9 @@ int flat_attn_unfused(const void* Q, const void* K, const void* V, void* O,
  * cost model (section 6.1) and discusses what the row granularity trades (section 5.3: fewer query rows per
  * tile re-fetch the keys more often and fill the compute array less; more rows need more on-chip memory).
  * Here the exploration is done by measurement: the library is built with several shapes per head dimension,
- * flat_attn_fwd uses index 0 (no other shape is ahead of it by more than the run-to-run spread over the measured
- * problems), and flat_attn_fwd_tile runs any of them so that the choice can be re-timed.
+ * flat_attn_fwd uses index 0, except for launches of few row blocks (at most 128 blocks of 256 query rows; 256
+ * with the causal mask at d = 64, 192 at d = 128), where the 128-row shape (d = 64: index 7, d = 128: index 2)
+ * measures 1.3-1.5 times faster; flat_attn_fwd_tile runs any shape so that the choice can be re-timed.
  *   flat_attn_tile_shape_count(d): number of shapes for head dimension d (0 if d is not one of 32, 64, 96, 128, 256).
  *   flat_attn_tile_shape_get: fills *out (HOST pointer) for 0 <= index < count; FLAT_ERR_SHAPE otherwise.
  *   flat_attn_tile_shape_occupancy: workgroups of that shape resident per compute unit on the current

@@ -79,13 +79,17 @@ hipError_t launch_fwd_bf16_tile(const void* Q, const void* K, const void* V, voi
     return e ? e->launch(Q, K, V, O, BH, prob, scale, causal, stream) : hipErrorInvalidValue;
 }
 
-// The shape flat_attn_fwd / flat_attn_fwd_cross run: index 0 everywhere.  The measured sweeps (python -m
-// paper_2107_06419_amd.tile_sweep, and causal problems from 2K to 32K positions with 7 to 256 heads) show no other
-// shape ahead by more than the run-to-run spread except the 512-row shape (index 3) at d = 64 with the causal mask
-// when B*H*ceil(N/512) is exactly 512 (3 %); with more or fewer row blocks the same shape loses 2-15 %, so no rule
-// is built on it.  The function stays as the one place where a measured rule would go.
+// The shape flat_attn_fwd / flat_attn_fwd_cross run: index 0, except for problems too small to give every compute
+// unit a 256-row workgroup.  Measured (1 to 128 heads, 128 to 4096 positions, both masks): with at most 128 blocks of
+// 256 query rows (256 with the causal mask at d = 64, 192 at d = 128) the 128-row shapes (d = 64: index 7, d = 128:
+// index 2) are 1.3-1.5 times faster, simply because twice as many compute units work; from 256 row blocks (512
+// causal) on they lose 5-15 %, and at no size is any other shape ahead of index 0 by more than the run-to-run spread
+// (the 512-row shape leads by 3 % for d = 64, causal, when B*H*ceil(N/512) is exactly 512, and trails by 2-15 % with
+// more or fewer row blocks: no rule is built on that).
 int default_tile_shape(int BH, int Nq, int d, int causal) {
-    (void)BH, (void)Nq, (void)d, (void)causal;
+    const long long blocks = (long long)BH * (((long long)Nq + 255) / 256);  // 256-row blocks in the launch
+    if (d == 64 && Nq > 256 && blocks <= (causal ? 256 : 128)) return 7;
+    if (d == 128 && Nq > 128 && blocks <= (causal ? 192 : 128)) return 2;
     return 0;
 }
 

@@ -1,10 +1,12 @@
-"""Measured tile-shape sweep of the fused bf16 kernel:  python -m paper_2107_06419_amd.tile_sweep [--out FILE]
+"""Measured tile-shape sweep of the fused bf16 kernel:  python -m paper_2107_06419_amd.tile_sweep [--small] [--out FILE]
 
 The paper chooses tile sizes by exhaustive search over a cost model (section 6.1, map-space exploration)
 and names the trade-off of the row granularity (section 5.3).  This tool does the search by timing: every
 tile shape the library was built with (flat_attn_tile_shape_*) runs on a set of problem shapes through
 flat_attn_fwd_tile, and the table of times is printed as Markdown.  Each shape's output is compared with
 the default shape's (index 0) on the same input, so a row in the table is also a consistency check.
+With --small it times launches of few row blocks instead (1 to 128 heads of 128 to 4096 positions), the 256-row
+default shape against the 128-row shapes: the table the small-launch rule of flat_attn_fwd was read off.
 Needs a GPU; inputs are the seeded synthetic tensors of paper_2107_06419_amd.synth.
 """
 from __future__ import annotations
@@ -56,11 +58,76 @@ def time_launch(fn, flops: float, min_warm_ms: float = 40.0, reps: int = 30) -> 
     return e0.elapsed_time(e1) / reps
 
 
+def small_launches(reps: int) -> str:
+    """Median microseconds per launch of the default shape and the 128-row shapes on small problems."""
+    import statistics
+
+    import numpy as np
+    import torch
+
+    import paper_2107_06419_amd as fa
+    from paper_2107_06419_amd import synth
+
+    def dev(x):
+        return torch.from_numpy(synth.f32_to_bf16_bits(x).reshape(x.shape).view(np.int16)).cuda().view(torch.bfloat16)
+
+    def median_us(fn):
+        for _ in range(30):
+            fn()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        return statistics.median(a.elapsed_time(b) for a, b in ev) * 1e3
+
+    lines = ["One batch entry, BH heads of N positions; median of %d launches by HIP events after 30 warm-up launches, in" % reps,
+             "microseconds.  blocks = BH * ceil(N / 256), the workgroups of the default shape; the last column is the time of",
+             "shape 0 over the best time, with the best shape.", ""]
+    for d, shapes in ((64, (0, 5, 7)), (128, (0, 2))):
+        for i in shapes:
+            t = fa.flat_attn_tile_shape_get(d, i).as_dict()
+            lines.append(f"d = {d} shape {i}: {t['rows_per_workgroup']} rows ({t['wavefronts']} wavefronts x {t['rows_per_wavefront']}), "
+                         f"{t['lds_stages']} stages, {fa.flat_attn_tile_shape_occupancy(d, i)} workgroups per CU")
+    lines.append("")
+    for d, shapes in ((64, (0, 5, 7)), (128, (0, 2))):
+        for mask in (0, 1):
+            lines.append(f"### d = {d}, {'causal' if mask else 'no mask'}")
+            lines.append("")
+            lines.append("| N | BH | blocks | " + " | ".join(f"shape {i}" for i in shapes) + " | shape 0 / best |")
+            lines.append("|" + "---|" * (4 + len(shapes)))
+            for N in (128, 256, 512, 1024, 2048, 4096):
+                for BH in (4, 12, 32, 64, 128):
+                    if BH * N > 64 * 4096:
+                        continue
+                    w = synth.custom(f"small_{d}_{N}_{BH}", 1, BH, N, d, "bf16", mask, seed=977 + N + BH + d)
+                    q, k, v = synth.make_qkv(w)
+                    dq, dk, dv = dev(q), dev(k), dev(v)
+                    out = torch.empty_like(dq)
+                    ts = [median_us(lambda: fa.flat_attn_fwd_tile(dq, dk, dv, out, w.scale, mask, i)) for i in shapes]
+                    best = min(range(len(ts)), key=lambda i: ts[i])
+                    lines.append(f"| {N} | {BH} | {BH * ((N + 255) // 256)} | " + " | ".join(f"{t:.1f}" for t in ts) +
+                                 f" | {ts[0] / ts[best]:.2f} (shape {shapes[best]}) |")
+                    print(lines[-1], file=sys.stderr, flush=True)
+            lines.append("")
+    return "\n".join(lines)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default="", help="also write the Markdown table to this file")
     ap.add_argument("--reps", type=int, default=30)
+    ap.add_argument("--small", action="store_true", help="time small launches (default shape against the 128-row shapes) instead")
     args = ap.parse_args()
+    if args.small:
+        text = small_launches(max(args.reps, 40))
+        print(text)
+        if args.out:
+            with open(args.out, "w") as f:
+                f.write(text + "\n")
+        return 0
 
     import numpy as np
     import torch

@@ -144,6 +144,26 @@ def test_long_causal_d64_default_and_512_row_shape_match_the_oracle():
             check_close(to_host_f64(explicit[:, :, drows, :]), ref, "bf16", f"{w.name} shape {index}")
 
 
+@pytest.mark.parametrize("d,B,H,N,mask,index", [(64, 1, 12, 512, 0, 7), (64, 2, 64, 512, 1, 7), (64, 1, 129, 512, 0, 0), (64, 8, 16, 256, 0, 0),
+                                                (128, 1, 12, 1024, 0, 2), (128, 1, 48, 1024, 1, 2), (128, 1, 40, 1024, 0, 0)])
+def test_small_launches_take_the_128_row_shape(d, B, H, N, mask, index):
+    """flat_attn_fwd's choice of tile shape for launches of few row blocks, shown by bitwise equality with that shape
+    run explicitly, and the result compared with the oracle."""
+    import torch
+    import paper_2107_06419_amd as fa
+    w = synth.custom(f"small_{d}_{B}_{H}_{N}_{mask}", B, H, N, d, "bf16", mask, seed=3100 + H + N + mask)
+    q, k, v = synth.make_qkv(w)
+    out = run_entry("fused", w, q, k, v)
+    rows = sample_rows(w.N, 12, seed=w.seed)
+    check_close(to_host_f64(out[:, :, torch.from_numpy(rows).cuda(), :]), oracle_rows(w, q, k, v, rows=rows), "bf16", w.name)
+    dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+    explicit = torch.full_like(dq, float("nan"))
+    fa.flat_attn_fwd_tile(dq, dk, dv, explicit, w.scale, w.mask, index)
+    torch.cuda.synchronize()
+    assert fa.flat_attn_tile_shape_get(d, index).as_dict()["rows_per_workgroup"] == (256 if index == 0 else 128)
+    assert torch.equal(out.view(torch.int16), explicit.view(torch.int16))
+
+
 def test_largest_workload_every_row():
     """The 64K-key workload compared with the oracle on EVERY query row of every head (the sampled test above
     looks at a few dozen rows per head).  The oracle takes the rows in slices and reports after each, so a
@@ -362,7 +382,10 @@ def test_blocksparse_with_every_tile_is_bitwise_the_dense_kernel_and_empty_lists
         offs = np.arange(n_lists + 1, dtype=np.int64) * n_kt
         ids = np.tile(np.arange(n_kt, dtype=np.int64), n_lists)
         out = _run_blocksparse(w, q, k, v, offs, ids)
-        dense = run_entry("fused", w, q, k, v)
+        dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+        dense = torch.full_like(dq, float("nan"))
+        fa.flat_attn_fwd_tile(dq, dk, dv, dense, w.scale, 0, 0)  # the 256-row shape the block-sparse form is built on
+        torch.cuda.synchronize()
         assert torch.equal(out.view(torch.int16), dense.view(torch.int16))
         # row block 1 of every head sees nothing, the others only tile 3
         counts = np.ones(n_lists, dtype=np.int64)

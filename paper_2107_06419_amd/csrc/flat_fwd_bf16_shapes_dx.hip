@@ -8,7 +8,9 @@
 namespace flat {
 
 FLAT_INSTANTIATE_BF16_SHAPE(32, 2, 4, 4)
+FLAT_INSTANTIATE_BF16_SHAPE(32, 1, 4, 4)
 FLAT_INSTANTIATE_BF16_SHAPE(96, 1, 8, 3)
+FLAT_INSTANTIATE_BF16_SHAPE(96, 1, 4, 3)
 FLAT_INSTANTIATE_BF16_SHAPE(256, 1, 4, 4)
 
 hipError_t launch_fwd_bf16_sparse_dx(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,

@@ -30,8 +30,8 @@ const Entry kD64[] = {entry<64, 2, 4, 4>(), entry<64, 2, 4, 3>(), entry<64, 2, 4
                       // the key-tile axis: 128 keys per tile (512-row and 256-row workgroups), 32 keys per tile
                       entry<64, 2, 8, 3, 128>(), entry<64, 2, 8, 4, 128>(), entry<64, 2, 4, 3, 128>(), entry<64, 2, 4, 6, 32>()};
 const Entry kD128[] = {entry<128, 1, 8, 3>(), entry<128, 1, 8, 4>(), entry<128, 1, 4, 3>(), entry<128, 2, 4, 3>()};
-const Entry kD32[] = {entry<32, 2, 4, 4>()};
-const Entry kD96[] = {entry<96, 1, 8, 3>()};
+const Entry kD32[] = {entry<32, 2, 4, 4>(), entry<32, 1, 4, 4>()};
+const Entry kD96[] = {entry<96, 1, 8, 3>(), entry<96, 1, 4, 3>()};
 const Entry kD256[] = {entry<256, 1, 4, 4>()};
 
 const Entry* table(int d) {
@@ -81,8 +81,8 @@ hipError_t launch_fwd_bf16_tile(const void* Q, const void* K, const void* V, voi
 
 // The shape flat_attn_fwd / flat_attn_fwd_cross run: index 0, except for problems too small to give every compute
 // unit a 256-row workgroup.  Measured (1 to 128 heads, 128 to 4096 positions, both masks): with at most 128 blocks of
-// 256 query rows (256 with the causal mask at d = 64, 192 at d = 128) the 128-row shapes (d = 64: index 7, d = 128:
-// index 2) are 1.3-1.5 times faster, simply because twice as many compute units work; from 256 row blocks (512
+// 256 query rows (256 with the causal mask at d = 32 and 64, 192 at d = 96 and 128) the 128-row shapes (d = 64: index 7,
+// d = 128: index 2, d = 32 and 96: index 1) are 1.3-1.5 times faster, simply because twice as many compute units work; from 256 row blocks (512
 // causal) on they lose 5-15 %, and at no size is any other shape ahead of index 0 by more than the run-to-run spread
 // (the 512-row shape leads by 3 % for d = 64, causal, when B*H*ceil(N/512) is exactly 512, and trails by 2-15 % with
 // more or fewer row blocks: no rule is built on that).
@@ -90,6 +90,8 @@ int default_tile_shape(int BH, int Nq, int d, int causal) {
     const long long blocks = (long long)BH * (((long long)Nq + 255) / 256);  // 256-row blocks in the launch
     if (d == 64 && Nq > 256 && blocks <= (causal ? 256 : 128)) return 7;
     if (d == 128 && Nq > 128 && blocks <= (causal ? 192 : 128)) return 2;
+    if (d == 32 && Nq > 512 && blocks <= (causal ? 256 : 128)) return 1;
+    if (d == 96 && Nq > 128 && blocks <= (causal ? 192 : 128)) return 1;
     return 0;
 }
 

@@ -86,13 +86,13 @@ def small_launches(reps: int) -> str:
     lines = ["One batch entry, BH heads of N positions; median of %d launches by HIP events after 30 warm-up launches, in" % reps,
              "microseconds.  blocks = BH * ceil(N / 256), the workgroups of the default shape; the last column is the time of",
              "shape 0 over the best time, with the best shape.", ""]
-    for d, shapes in ((64, (0, 5, 7)), (128, (0, 2))):
+    for d, shapes in ((64, (0, 5, 7)), (128, (0, 2)), (32, (0, 1)), (96, (0, 1))):
         for i in shapes:
             t = fa.flat_attn_tile_shape_get(d, i).as_dict()
             lines.append(f"d = {d} shape {i}: {t['rows_per_workgroup']} rows ({t['wavefronts']} wavefronts x {t['rows_per_wavefront']}), "
                          f"{t['lds_stages']} stages, {fa.flat_attn_tile_shape_occupancy(d, i)} workgroups per CU")
     lines.append("")
-    for d, shapes in ((64, (0, 5, 7)), (128, (0, 2))):
+    for d, shapes in ((64, (0, 5, 7)), (128, (0, 2)), (32, (0, 1)), (96, (0, 1))):
         for mask in (0, 1):
             lines.append(f"### d = {d}, {'causal' if mask else 'no mask'}")
             lines.append("")

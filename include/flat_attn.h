@@ -174,9 +174,10 @@ int flat_attn_unfused(const void* Q, const void* K, const void* V, void* O,
  * cost model (section 6.1) and discusses what the row granularity trades (section 5.3: fewer query rows per
  * tile re-fetch the keys more often and fill the compute array less; more rows need more on-chip memory).
  * Here the exploration is done by measurement: the library is built with several shapes per head dimension,
- * flat_attn_fwd uses index 0, except for launches of few row blocks (at most 128 blocks of 256 query rows; 256
- * with the causal mask at d = 32 and 64, 192 at d = 96 and 128), where the 128-row shape (d = 64: index 7, d = 128:
- * index 2, d = 32 and 96: index 1) measures 1.3-1.5 times faster; flat_attn_fwd_tile runs any shape so that the
+ * flat_attn_fwd uses index 0, except where the 128-row shape (d = 64: index 7, d = 128: index 2, d = 32 and 96:
+ * index 1) measures ahead: launches of few row blocks (at most 128 blocks of 256 query rows; 256 with the causal
+ * mask at d = 32 and 64, 192 at d = 96 and 128: 1.3-1.5 times faster), d = 64 with the causal mask up to 4096
+ * positions and 1024 row blocks, and d = 32 for short sequences.  flat_attn_fwd_tile runs any shape so that the
  * choice can be re-timed.
  *   flat_attn_tile_shape_count(d): number of shapes for head dimension d (0 if d is not one of 32, 64, 96, 128, 256).
  *   flat_attn_tile_shape_get: fills *out (HOST pointer) for 0 <= index < count; FLAT_ERR_SHAPE otherwise.

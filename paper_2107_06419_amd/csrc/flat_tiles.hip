@@ -79,20 +79,30 @@ hipError_t launch_fwd_bf16_tile(const void* Q, const void* K, const void* V, voi
     return e ? e->launch(Q, K, V, O, BH, prob, scale, causal, stream) : hipErrorInvalidValue;
 }
 
-// The shape flat_attn_fwd / flat_attn_fwd_cross run: index 0, except for problems too small to give every compute
-// unit a 256-row workgroup.  Measured (1 to 128 heads, 128 to 4096 positions, both masks): with at most 128 blocks of
-// 256 query rows (256 with the causal mask at d = 32 and 64, 192 at d = 96 and 128) the 128-row shapes (d = 64: index 7,
-// d = 128: index 2, d = 32 and 96: index 1) are 1.3-1.5 times faster, simply because twice as many compute units work; from 256 row blocks (512
-// causal) on they lose 5-15 %, and at no size is any other shape ahead of index 0 by more than the run-to-run spread
-// (the 512-row shape leads by 3 % for d = 64, causal, when B*H*ceil(N/512) is exactly 512, and trails by 2-15 % with
-// more or fewer row blocks: no rule is built on that).
+// The shape flat_attn_fwd / flat_attn_fwd_cross run: index 0, except where a measured sweep (python -m
+// paper_2107_06419_amd.tile_sweep --small: 1 to 512 heads of 128 to 8192 positions, both masks, several machines)
+// shows the 128-row shape of the head dimension ahead:
+//   * launches too small to give every compute unit a 256-row workgroup - at most 128 blocks of 256 query rows (causal:
+//     256 at d = 32 / 64, 192 at d = 96 / 128): 1.3-1.5 times faster, simply because twice as many compute units work;
+//   * d = 64 with the causal mask, up to 4096 positions and 1024 row blocks: ahead by up to 15 %, never behind;
+//   * d = 32 (the vector side is the longer pole there and three workgroups per compute unit hide more of it): with
+//     the causal mask up to 8192 positions (4-18 %), without it up to 4096 positions and 1024 row blocks (6 %).
+// Beyond these ranges the 128-row shapes lose 1-15 %.  No other shape is ahead of index 0 by more than the
+// run-to-run spread (the 512-row shape leads by 3 % for d = 64, causal, when B*H*ceil(N/512) is exactly 512, and
+// trails by 2-15 % with more or fewer row blocks: no rule is built on that).
 int default_tile_shape(int BH, int Nq, int d, int causal) {
     const long long blocks = (long long)BH * (((long long)Nq + 255) / 256);  // 256-row blocks in the launch
-    if (d == 64 && Nq > 256 && blocks <= (causal ? 256 : 128)) return 7;
-    if (d == 128 && Nq > 128 && blocks <= (causal ? 192 : 128)) return 2;
-    if (d == 32 && Nq > 512 && blocks <= (causal ? 256 : 128)) return 1;
-    if (d == 96 && Nq > 128 && blocks <= (causal ? 192 : 128)) return 1;
-    return 0;
+    switch (d) {
+        case 32:
+            if (causal) return (Nq > 128 && Nq <= 8192) ? 1 : 0;
+            return (Nq > 512 && ((Nq <= 4096 && blocks <= 1024) || blocks <= 128)) ? 1 : 0;
+        case 64:
+            if (causal) return (Nq > 256 && blocks <= (Nq <= 4096 ? 1024 : 256)) ? 7 : 0;
+            return (Nq > 256 && blocks <= 128) ? 7 : 0;
+        case 96: return (Nq > 128 && blocks <= (causal ? 192 : 128)) ? 1 : 0;
+        case 128: return (Nq > 128 && blocks <= (causal ? 192 : 128)) ? 2 : 0;
+        default: return 0;
+    }
 }
 
 hipError_t launch_fwd_bf16(const void* Q, const void* K, const void* V, void* O, int BH, const Bf16Problem& prob, int d,

@@ -146,7 +146,8 @@ def test_long_causal_d64_default_and_512_row_shape_match_the_oracle():
 
 @pytest.mark.parametrize("d,B,H,N,mask,index", [(64, 1, 12, 512, 0, 7), (64, 2, 64, 512, 1, 7), (64, 1, 129, 512, 0, 0), (64, 8, 16, 256, 0, 0),
                                                 (128, 1, 12, 1024, 0, 2), (128, 1, 48, 1024, 1, 2), (128, 1, 40, 1024, 0, 0),
-                                                (32, 1, 12, 1024, 0, 1), (32, 1, 12, 512, 0, 0), (96, 1, 12, 640, 1, 1), (96, 1, 70, 700, 0, 0)])
+                                                (32, 1, 12, 1024, 0, 1), (32, 1, 12, 512, 0, 0), (96, 1, 12, 640, 1, 1), (96, 1, 70, 700, 0, 0),
+                                                (64, 1, 128, 2048, 1, 7), (64, 1, 96, 4096, 1, 0), (32, 2, 16, 8192, 1, 1), (32, 1, 40, 8192, 0, 0)])
 def test_small_launches_take_the_128_row_shape(d, B, H, N, mask, index):
     """flat_attn_fwd's choice of tile shape for launches of few row blocks, shown by bitwise equality with that shape
     run explicitly, and the result compared with the oracle."""

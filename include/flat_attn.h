@@ -184,6 +184,8 @@ int flat_attn_unfused(const void* Q, const void* K, const void* V, void* O,
  *   flat_attn_tile_shape_occupancy: workgroups of that shape resident per compute unit on the current
  *     device (registers and LDS permitting), or a negative flat_status; the only one of the three that
  *     needs a GPU.
+ *   flat_attn_tile_shape_default: the index flat_attn_fwd (N = Nq) and flat_attn_fwd_cross (Nq query rows) take for a
+ *     problem, or a negative flat_status; host arithmetic only.
  *   flat_attn_fwd_tile: flat_attn_fwd with the shape chosen by the caller; same arguments, checks and
  *     result tolerance (different shapes sum in different orders, so results differ in the last bits).
  */
@@ -200,6 +202,7 @@ typedef struct {
 int flat_attn_tile_shape_count(int d);
 int flat_attn_tile_shape_get(int d, int index, flat_tile_shape* out);
 int flat_attn_tile_shape_occupancy(int d, int index);
+int flat_attn_tile_shape_default(int B, int H, int Nq, int d, int mask_kind);
 int flat_attn_fwd_tile(const void* Q, const void* K, const void* V, void* O,
                        int B, int H, int N, int d, float scale, int mask_kind, int tile_shape, void* stream);
 

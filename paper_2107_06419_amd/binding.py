@@ -117,6 +117,8 @@ def load_library():
     lib.flat_attn_tile_shape_get.argtypes = [i, i, ctypes.POINTER(FlatTileShape)]
     lib.flat_attn_tile_shape_occupancy.restype = i
     lib.flat_attn_tile_shape_occupancy.argtypes = [i, i]
+    lib.flat_attn_tile_shape_default.restype = i
+    lib.flat_attn_tile_shape_default.argtypes = [i, i, i, i, i]
     lib.flat_attn_fwd_tile.restype = i
     lib.flat_attn_fwd_tile.argtypes = [vp, vp, vp, vp, i, i, i, i, f, i, i, vp]
     lib.flat_attn_status_string.restype = ctypes.c_char_p
@@ -290,6 +292,14 @@ def flat_attn_tile_shape_get(d: int, index: int) -> FlatTileShape:
 def flat_attn_tile_shape_occupancy(d: int, index: int) -> int:
     """Workgroups of the shape resident per compute unit on the current device (needs a GPU)."""
     n = int(load_library().flat_attn_tile_shape_occupancy(int(d), int(index)))
+    if n < 0:
+        _check(n)
+    return n
+
+
+def flat_attn_tile_shape_default(B: int, H: int, Nq: int, d: int, mask_kind: int = FLAT_MASK_NONE) -> int:
+    """Index of the tile shape flat_attn_fwd / flat_attn_fwd_cross take for this problem (host arithmetic only)."""
+    n = int(load_library().flat_attn_tile_shape_default(int(B), int(H), int(Nq), int(d), int(mask_kind)))
     if n < 0:
         _check(n)
     return n

@@ -235,6 +235,13 @@ int flat_attn_tile_shape_occupancy(int d, int index) {
     return flat::tile_shape_occupancy(d, index, &n) == hipSuccess ? n : FLAT_ERR_HIP;
 }
 
+int flat_attn_tile_shape_default(int B, int H, int Nq, int d, int mask_kind) {
+    if (B <= 0 || H <= 0 || Nq <= 0 || (long long)B * H > 0x7fffffffLL) return FLAT_ERR_SHAPE;
+    if (!fused_bf16_head_dim(d)) return FLAT_ERR_UNSUPPORTED;
+    if (mask_kind != FLAT_MASK_NONE && mask_kind != FLAT_MASK_CAUSAL) return FLAT_ERR_UNSUPPORTED;
+    return flat::default_tile_shape(B * H, Nq, d, mask_kind == FLAT_MASK_CAUSAL);
+}
+
 int flat_attn_fwd_tile(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
                        int mask_kind, int tile_shape, void* stream) {
     const int rc = check_common(Q, K, V, O, B, H, N, d, scale, mask_kind, 2, true);

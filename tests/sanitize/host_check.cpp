@@ -40,6 +40,7 @@ bool tile_shape(int d, int index, TileShape* out) {
     return true;
 }
 hipError_t tile_shape_occupancy(int, int, int* n) { *n = 2; return hipSuccess; }
+int default_tile_shape(int, int, int, int) { return 0; }
 hipError_t launch_fwd_f32(const float*, const float*, const float*, float*, int, int, int, float, int, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_unfused_bf16(const void*, const void*, const void*, void*, int, int, int, float, int, float*, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_mfma_probe(float*, int, int, hipStream_t) { ++g_launches; return hipSuccess; }

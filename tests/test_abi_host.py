@@ -125,6 +125,18 @@ def test_tile_shape_table_is_consistent():
             assert lib.flat_attn_tile_shape_occupancy(d, bad) == -2
     assert lib.flat_attn_tile_shape_get(64, 0, None) == -1
     assert lib.flat_attn_tile_shape_occupancy(80, 0) == -3
+    # the default shape is host arithmetic: large launches take index 0, small ones the 128-row shape
+    assert fa.flat_attn_tile_shape_default(1, 16, 16384, 64, 0) == 0 and fa.flat_attn_tile_shape_default(2, 8, 8192, 128, 1) == 0
+    assert fa.flat_attn_tile_shape_default(1, 12, 512, 64, 0) == 7 and fa.flat_attn_tile_shape_default(1, 12, 512, 128, 1) == 2
+    assert fa.flat_attn_tile_shape_default(1, 12, 256, 64, 0) == 0 and fa.flat_attn_tile_shape_default(1, 129, 512, 64, 0) == 0
+    for d in (32, 64, 96, 128, 256):
+        for B, H, N, mask in ((1, 1, 1, 0), (3, 7, 300, 1), (1, 12, 512, 0), (64, 12, 512, 1), (1, 16, 16384, 0), (2147483, 1000, 77, 1)):
+            idx = fa.flat_attn_tile_shape_default(B, H, N, d, mask)
+            assert 0 <= idx < fa.flat_attn_tile_shape_count(d)
+            if idx:
+                assert fa.flat_attn_tile_shape_get(d, idx).as_dict()["rows_per_workgroup"] == 128
+    assert lib.flat_attn_tile_shape_default(0, 1, 1, 64, 0) == -2 and lib.flat_attn_tile_shape_default(1, 1, 1, 80, 0) == -3
+    assert lib.flat_attn_tile_shape_default(1, 1, 1, 64, 2) == -3 and lib.flat_attn_tile_shape_default(65536, 65536, 1, 64, 0) == -2
     d64, d128 = fa.flat_attn_tile_shape_get(64, 0).as_dict(), fa.flat_attn_tile_shape_get(128, 0).as_dict()
     assert (d64["rows_per_workgroup"], d64["wavefronts"], d64["lds_stages"]) == (256, 4, 4)
     assert (d128["rows_per_workgroup"], d128["wavefronts"], d128["lds_stages"]) == (256, 8, 3)

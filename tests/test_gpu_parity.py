@@ -40,8 +40,47 @@ def test_fused_bf16_matches_oracle(B, H, N, d, mask):
     w = synth.custom(f"small_{B}_{H}_{N}_{d}_{mask}", B, H, N, d, "bf16", mask, seed=1000 + N + d + mask)
     q, k, v = synth.make_qkv(w)
     print(f"case fused bf16 {w}", flush=True)
-    got = to_host_f64(run_entry("fused", w, q, k, v))
-    check_close(got, oracle_rows(w, q, k, v), "bf16", w.name)
+    ref = oracle_rows(w, q, k, v)
+    check_close(to_host_f64(run_entry("fused", w, q, k, v)), ref, "bf16", w.name)
+    # launches this small take the 128-row shape where the head size has one: the 256-row shape (index 0) that large
+    # launches run goes through the same ragged cases explicitly
+    import torch
+    import paper_2107_06419_amd as fa
+    dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+    out = torch.full_like(dq, float("nan"))
+    fa.flat_attn_fwd_tile(dq, dk, dv, out, w.scale, w.mask, 0)
+    torch.cuda.synchronize()
+    check_close(to_host_f64(out), ref, "bf16", w.name + " shape 0")
+
+
+@pytest.mark.parametrize("d", [32, 64, 96, 128, 256])
+@pytest.mark.parametrize("mask", [0, 1])
+def test_fused_cross_many_heads_on_the_256_row_shape(d, mask):
+    """Cross-length problems with key counts, ragged in both lengths, with enough heads that flat_attn_fwd_cross takes
+    the 256-row shape large launches run (few heads take the 128-row shape); d = 32 with the causal mask has no such
+    range below 8192 positions and runs its 128-row shape here."""
+    import torch
+    import paper_2107_06419_amd as fa
+    B, H, Nq, Nk = 6, 100, 257, 900
+    expect = 1 if (d == 32 and mask == 1) else 0
+    assert fa.flat_attn_tile_shape_default(B, H, Nq, d, mask) == expect
+    rng = np.random.default_rng(77 + d + mask)
+    lens = [int(x) for x in rng.integers(Nq if mask else 1, Nk + 1, size=B)]
+    lens[0], lens[1] = Nk, (Nq if mask else 1)
+
+    def rounded(shape, tid):
+        x = synth.tensor_f32(shape, 6100 + d + mask, tid, "normal", 1.0)
+        return synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(x)).reshape(shape)
+
+    q, k, v = rounded((B, H, Nq, d), 0), rounded((B, H, Nk, d), 1), rounded((B, H, Nk, d), 2)
+    dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+    out = torch.full_like(dq, float("nan"))
+    scale = float(np.float32(d ** -0.5))
+    print(f"case cross many heads d={d} mask={mask} lens={lens}", flush=True)
+    fa.flat_attn_fwd_cross(dq, dk, dv, out, scale, mask, torch.tensor(lens, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    ref = oracle.attention_cross(q, k, v, scale, mask, kv_lens=np.array(lens))
+    check_close(to_host_f64(out), ref, "bf16", f"cross many heads d={d} mask={mask}")
 
 
 @pytest.mark.parametrize("B,H,N", SMALL_SHAPES)
@@ -163,6 +202,7 @@ def test_small_launches_take_the_128_row_shape(d, B, H, N, mask, index):
     fa.flat_attn_fwd_tile(dq, dk, dv, explicit, w.scale, w.mask, index)
     torch.cuda.synchronize()
     assert fa.flat_attn_tile_shape_get(d, index).as_dict()["rows_per_workgroup"] == (256 if index == 0 else 128)
+    assert fa.flat_attn_tile_shape_default(B, H, N, d, mask) == index
     assert torch.equal(out.view(torch.int16), explicit.view(torch.int16))
 
 
@@ -529,6 +569,10 @@ def test_randomized_small_problems_all_bf16_entry_points():
             fa.flat_attn_fwd(dq, dk, dv, out2, scale, mask)
             torch.cuda.synchronize()
             assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+            out0 = torch.full_like(dq, float("nan"))
+            fa.flat_attn_fwd_tile(dq, dk, dv, out0, scale, mask, 0)
+            torch.cuda.synchronize()
+            check_close(to_host_f64(out0), ref, "bf16", f"random shape 0 {case}")
             if d in (64, 128):
                 ws = torch.empty(fa.flat_attn_unfused_workspace_bytes(B, H, Nk, d) // 4, dtype=torch.float32, device="cuda")
                 out3 = torch.full_like(dq, float("nan"))

@@ -57,6 +57,14 @@ def main() -> int:
         for _ in range(args.reps):
             fa.flat_attn_fwd_splitkv(tq, tk, tv, to, scale, 1, None, 0, ws)
         torch.cuda.synchronize()
+        if args.copy_mib > 0:  # the copy of known size that calibrates FETCH_SIZE / WRITE_SIZE
+            n = args.copy_mib * (1 << 20) // 4
+            src = torch.ones(n, dtype=torch.float32, device="cuda")
+            dst = torch.empty_like(src)
+            torch.cuda.synchronize()
+            for _ in range(args.reps):
+                dst.copy_(src)
+            torch.cuda.synchronize()
         print("profile_driver done cache", args.cache, "splits", fa.flat_attn_fwd_splitkv_splits(1, H, Nq, Nk, d, 0), flush=True)
         return 0
     if args.shape:
